@@ -1,0 +1,166 @@
+/*
+ * sa.h - C ABI of the SampleAttention prefill hot path for AMD MI355X (gfx950).
+ *
+ * The library computes causal prefill attention under an adaptive structured
+ * sparse mask (SampleAttention, arXiv 2406.15486, Algorithm 1):
+ *
+ *   stage 1  sa_sample_scores   exact causal softmax rows of a sampled subset
+ *                               of queries, accumulated into per-key column
+ *                               scores and per-offset slash scores
+ *   stage 2  sa_select_strips   fewest column / slash strips whose score mass
+ *                               reaches the CRA thresholds alpha_c / alpha_s
+ *   attend   sa_sparse_attn     flash-style attention over the merged mask
+ *   baseline sa_dense_attn      dense causal flash-style attention (Eq. 1-2)
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *   never allocates, frees or keeps them; scratch memory comes only from the
+ *   caller's workspace (size from sa_workspace_bytes, 256-byte aligned).
+ * - Tensors are row-major and contiguous: Q and O are [batch, n_q_heads,
+ *   seq_len, head_dim]; K and V are [batch, n_kv_heads, seq_len, head_dim];
+ *   query head h reads KV head h / (n_q_heads / n_kv_heads) (grouped-query
+ *   attention, Sec. 5.1).  Q, K, V are bf16.  Per-head vectors (scores, index
+ *   lists, lse) are [batch * n_q_heads, seq_len] (or [.., n_sample_rows]).
+ * - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   Calls only enqueue work and return without synchronising; counts and
+ *   index lists stay on the device, so the stages chain without a host sync.
+ * - Errors are return codes.  All argument checks (null pointers, shapes,
+ *   ranges, workspace size) run on the host before anything is launched, so
+ *   they work on a machine without a GPU.  SA_ERR_DEVICE reports a failed
+ *   launch (hipGetLastError).
+ * - Two calls that share a workspace must not overlap in time.
+ */
+#ifndef SA_H
+#define SA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SA_OK = 0,
+  SA_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, value out of range */
+  SA_ERR_UNSUPPORTED = 2, /* a valid request this build does not implement       */
+  SA_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or too small          */
+  SA_ERR_DEVICE = 4       /* the HIP runtime reported an error on launch         */
+} sa_status;
+
+/* Problem shape.  head_dim must be 128 and causal must be 1 (the method is
+ * defined for decoder-only prefill); n_q_heads % n_kv_heads == 0. */
+typedef struct {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t seq_len;
+  int32_t head_dim;
+  int32_t causal;
+  float softmax_scale; /* 0 -> 1/sqrt(head_dim) (Eq. 1) */
+} sa_shape;
+
+/* Stage-1 sampling.  n_sample_rows: the last n rows of the sequence are the
+ * sampled queries (Algorithm 1 with chunk_n = 1), 1 <= n <= seq_len and a
+ * multiple of 32 unless it equals seq_len.  n_chunks and granularity are the
+ * paper's chunk_n and blk; this build implements n_chunks == 1 and
+ * granularity == 1 (per-key / per-offset strips) and returns
+ * SA_ERR_UNSUPPORTED otherwise. */
+typedef struct {
+  int32_t n_sample_rows;
+  int32_t n_chunks;
+  int32_t granularity;
+} sa_sampling;
+
+typedef enum { SA_OUT_BF16 = 0, SA_OUT_F32 = 1 } sa_out_dtype;
+
+typedef enum {
+  SA_OP_SAMPLE_SCORES = 0,
+  SA_OP_SELECT_STRIPS = 1,
+  SA_OP_SPARSE_ATTN = 2,
+  SA_OP_DENSE_ATTN = 3
+} sa_op;
+
+/* Bytes of device workspace `op` needs for this shape (sampling may be NULL
+ * for ops that do not sample).  Returns 0 for invalid arguments.  Host only. */
+size_t sa_workspace_bytes(int op, const sa_shape* shape, const sa_sampling* sampling);
+
+/* 64 * ceil(ratio * seq_len / 64), clamped to [min(64, seq_len), seq_len]:
+ * the sampled-row count for a sample ratio.  Host only. */
+int32_t sa_rows_from_ratio(int32_t seq_len, float ratio);
+
+/*
+ * Stage 1 (Algorithm 1 "Query-Guided Chunked Attention Sampling", Sec. 4.2).
+ * For every query head and every sampled row i in R = [S - n, S):
+ *   p_ij = softmax_j(q_i . k_j * scale), j <= i            (exact, causal)
+ *   col_scores[h, j]   = sum_{i in R, i >= j} p_ij
+ *   slash_scores[h, o] = sum_{i in R, i >= o} p_{i, i-o}    (offset o = i - j)
+ * in:  q, k (bf16, layouts above)
+ * out: col_scores, slash_scores  fp32 [batch*n_q_heads, seq_len]
+ *      row_lse (nullable)        fp32 [batch*n_q_heads, n] natural-log
+ *                                sum-exp of each sampled row
+ * The sums are formed in a fixed order: repeated calls give identical bits.
+ */
+sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
+                           const void* q, const void* k,
+                           float* col_scores, float* slash_scores, float* row_lse,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Stage 2 (Algorithm 1 "Score-Based Key-Value Block Filtering", Sec. 4.3).
+ * Independently per head and per direction: order candidates by (score
+ * descending, index ascending), take the smallest k >= 0 whose first-k score
+ * sum (fp64) reaches alpha * total; alpha >= 1 keeps all seq_len candidates,
+ * alpha == 0 keeps none.  Scores must be finite and >= 0.
+ * in:  col_scores, slash_scores  fp32 [batch*n_q_heads, seq_len]
+ *      alpha_c, alpha_s          CRA thresholds, each >= 0
+ * out: col_idx, slash_idx  int32 [batch*n_q_heads, seq_len]; the first cnt[h]
+ *                          entries of row h are the kept indices in ASCENDING
+ *                          order, the rest is unspecified
+ *      col_cnt, slash_cnt  int32 [batch*n_q_heads]
+ */
+sa_status sa_select_strips(const sa_shape* shape,
+                           const float* col_scores, const float* slash_scores,
+                           float alpha_c, float alpha_s,
+                           int32_t* col_idx, int32_t* col_cnt,
+                           int32_t* slash_idx, int32_t* slash_cnt,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Merge + attend (Algorithm 1 merge_index and sparse_flash_attn; Eq. 3 with
+ * masked entries contributing exactly zero).  The mask of head h is
+ *   M[i, j] = (j <= i) and (j in I_c[h]  or  (i-j) in I_s[h]  or  i-j < local_window)
+ * and O_i = softmax over {j : M[i,j]} of (q_i . k_j * scale) times V.
+ * in:  q, k, v; col_idx/col_cnt, slash_idx/slash_cnt as written by
+ *      sa_select_strips - or any other ascending, duplicate-free lists with
+ *      entries in [0, seq_len) and counts in [0, seq_len];
+ *      local_window >= 1 (every row keeps at least its own key)
+ * out: out      [batch, n_q_heads, seq_len, head_dim], bf16 or fp32
+ *      out_lse  (nullable) fp32 [batch*n_q_heads, seq_len], natural log of
+ *               the masked sum-exp
+ *      tiles    (nullable) uint64 [batch*n_q_heads]: number of 128x64
+ *               (query x key) score tiles the kernel computed for the head
+ */
+sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
+                         const int32_t* col_idx, const int32_t* col_cnt,
+                         const int32_t* slash_idx, const int32_t* slash_cnt,
+                         int32_t local_window,
+                         void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Dense causal attention (Eq. 1-2 with keys j <= i), the in-library baseline
+ * the sparse path is compared against.  Same layouts and outputs as above.
+ */
+sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
+                        void* out, int out_dtype, float* out_lse,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+const char* sa_status_string(int status);
+int sa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SA_H */

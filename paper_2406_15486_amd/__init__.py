@@ -1,0 +1,22 @@
+"""MI355X-native SampleAttention prefill hot path.
+
+Thin Python binding over the C-ABI library ``libsampleattn.so`` (hand-written
+HIP kernels for gfx950).  The binding only marshals arguments: every step of
+the path runs in the library's kernels.  PyTorch supplies device memory and the
+stream, nothing else.
+"""
+from .binding import (  # noqa: F401
+    SA_OUT_BF16,
+    SA_OUT_F32,
+    SaError,
+    Shape,
+    lib_path,
+    load_library,
+    sa_dense_attn,
+    sa_rows_from_ratio,
+    sa_sample_scores,
+    sa_select_strips,
+    sa_sparse_attn,
+    sa_workspace_bytes,
+    sample_attention,
+)

@@ -1,0 +1,238 @@
+"""ctypes binding of the C ABI declared in include/sa.h.
+
+Same names as the C entry points.  Tensors are torch CUDA tensors (device
+memory only); the current torch stream is passed to the library.  There is no
+fallback: if the shared library is missing the import of any entry point
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libsampleattn.so"
+
+SA_OUT_BF16, SA_OUT_F32 = 0, 1
+SA_OP_SAMPLE_SCORES, SA_OP_SELECT_STRIPS, SA_OP_SPARSE_ATTN, SA_OP_DENSE_ATTN = 0, 1, 2, 3
+
+
+class SaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().sa_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("seq_len", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("causal", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float)]
+
+
+class _CSampling(ctypes.Structure):
+    _fields_ = [("n_sample_rows", ctypes.c_int32), ("n_chunks", ctypes.c_int32),
+                ("granularity", ctypes.c_int32)]
+
+
+@dataclass(frozen=True)
+class Shape:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    seq_len: int
+    head_dim: int = 128
+    causal: int = 1
+    softmax_scale: float = 0.0
+
+    def c(self) -> _CShape:
+        return _CShape(self.batch, self.n_q_heads, self.n_kv_heads, self.seq_len,
+                       self.head_dim, self.causal, self.softmax_scale)
+
+    @property
+    def n_bh(self) -> int:
+        return self.batch * self.n_q_heads
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree shared library; raise loudly if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it first (python -m paper_2406_15486_amd.build "
+            "or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(path)
+    vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    lib.sa_workspace_bytes.restype = ctypes.c_size_t
+    lib.sa_workspace_bytes.argtypes = [ctypes.c_int, ctypes.POINTER(_CShape), ctypes.POINTER(_CSampling)]
+    lib.sa_rows_from_ratio.restype = ctypes.c_int32
+    lib.sa_rows_from_ratio.argtypes = [ctypes.c_int32, ctypes.c_float]
+    lib.sa_sample_scores.restype = ctypes.c_int
+    lib.sa_sample_scores.argtypes = [ctypes.POINTER(_CShape), ctypes.POINTER(_CSampling), vp, vp,
+                                     f32p, f32p, f32p, vp, ctypes.c_size_t, vp]
+    lib.sa_select_strips.restype = ctypes.c_int
+    lib.sa_select_strips.argtypes = [ctypes.POINTER(_CShape), f32p, f32p, ctypes.c_float, ctypes.c_float,
+                                     i32p, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.sa_sparse_attn.restype = ctypes.c_int
+    lib.sa_sparse_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, i32p, i32p, i32p, i32p,
+                                   ctypes.c_int32, vp, ctypes.c_int, f32p, vp, vp, ctypes.c_size_t, vp]
+    lib.sa_dense_attn.restype = ctypes.c_int
+    lib.sa_dense_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p,
+                                  vp, ctypes.c_size_t, vp]
+    lib.sa_status_string.restype = ctypes.c_char_p
+    lib.sa_status_string.argtypes = [ctypes.c_int]
+    lib.sa_version.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------ helpers --
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(t: torch.Tensor, dtype, shape: Tuple[int, ...], name: str) -> None:
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected contiguous CUDA {dtype} tensor of shape {tuple(shape)}, "
+                         f"got {t.dtype} {tuple(t.shape)} on {t.device}")
+
+
+def _shape_of(q: torch.Tensor, k: torch.Tensor, scale: float) -> Shape:
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("q and k must be [batch, heads, seq, head_dim]")
+    return Shape(q.shape[0], q.shape[1], k.shape[1], q.shape[2], q.shape[3], 1, float(scale))
+
+
+def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def sa_workspace_bytes(op: int, shape: Shape, n_sample_rows: int = 0) -> int:
+    lib = load_library()
+    cs = shape.c()
+    sm = _CSampling(n_sample_rows, 1, 1)
+    return int(lib.sa_workspace_bytes(op, ctypes.byref(cs), ctypes.byref(sm)))
+
+
+def sa_rows_from_ratio(seq_len: int, ratio: float) -> int:
+    return int(load_library().sa_rows_from_ratio(seq_len, ratio))
+
+
+# -------------------------------------------------------------- entry points --
+def sa_sample_scores(q, k, n_sample_rows: int, scale: float = 0.0, workspace=None, want_lse=False):
+    """Stage 1: column and slash scores of the last ``n_sample_rows`` queries.
+    Returns (col [B*Hq, S] f32, slash [B*Hq, S] f32[, row_lse [B*Hq, n] f32])."""
+    lib = load_library()
+    sh = _shape_of(q, k, scale)
+    _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
+    _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
+    cs, sm = sh.c(), _CSampling(n_sample_rows, 1, 1)
+    need = int(lib.sa_workspace_bytes(SA_OP_SAMPLE_SCORES, ctypes.byref(cs), ctypes.byref(sm)))
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    col = torch.empty(sh.n_bh, sh.seq_len, dtype=torch.float32, device=q.device)
+    slash = torch.empty_like(col)
+    lse = torch.empty(sh.n_bh, max(n_sample_rows, 1), dtype=torch.float32, device=q.device) if want_lse else None
+    st = lib.sa_sample_scores(ctypes.byref(cs), ctypes.byref(sm), _ptr(q), _ptr(k), _ptr(col), _ptr(slash),
+                              _ptr(lse), _ptr(ws), ws.numel() if ws is not None else 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_sample_scores")
+    return (col, slash, lse) if want_lse else (col, slash)
+
+
+def sa_select_strips(col_scores, slash_scores, alpha_c: float, alpha_s: float, shape: Shape):
+    """Stage 2: returns (col_idx, col_cnt, slash_idx, slash_cnt) int32 device tensors."""
+    lib = load_library()
+    _check(col_scores, torch.float32, (shape.n_bh, shape.seq_len), "col_scores")
+    _check(slash_scores, torch.float32, (shape.n_bh, shape.seq_len), "slash_scores")
+    dev = col_scores.device
+    col_idx = torch.empty(shape.n_bh, shape.seq_len, dtype=torch.int32, device=dev)
+    slash_idx = torch.empty_like(col_idx)
+    col_cnt = torch.empty(shape.n_bh, dtype=torch.int32, device=dev)
+    slash_cnt = torch.empty_like(col_cnt)
+    cs = shape.c()
+    st = lib.sa_select_strips(ctypes.byref(cs), _ptr(col_scores), _ptr(slash_scores),
+                              ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
+                              _ptr(col_idx), _ptr(col_cnt), _ptr(slash_idx), _ptr(slash_cnt),
+                              None, 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_select_strips")
+    return col_idx, col_cnt, slash_idx, slash_cnt
+
+
+def sa_sparse_attn(q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window: int,
+                   scale: float = 0.0, out_dtype: int = SA_OUT_BF16, workspace=None,
+                   want_lse: bool = False, want_tiles: bool = False):
+    """Attention under the strip mask.  Returns (out, lse or None, tiles or None)."""
+    lib = load_library()
+    sh = _shape_of(q, k, scale)
+    _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
+    _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
+    _check(v, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "v")
+    for t, nm in ((col_idx, "col_idx"), (slash_idx, "slash_idx")):
+        _check(t, torch.int32, (sh.n_bh, sh.seq_len), nm)
+    for t, nm in ((col_cnt, "col_cnt"), (slash_cnt, "slash_cnt")):
+        _check(t, torch.int32, (sh.n_bh,), nm)
+    cs = sh.c()
+    need = int(lib.sa_workspace_bytes(SA_OP_SPARSE_ATTN, ctypes.byref(cs), None))
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    out = torch.empty(q.shape, dtype=torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16, device=q.device)
+    lse = torch.empty(sh.n_bh, sh.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
+    tiles = torch.empty(sh.n_bh, dtype=torch.int64, device=q.device) if want_tiles else None
+    st = lib.sa_sparse_attn(ctypes.byref(cs), _ptr(q), _ptr(k), _ptr(v), _ptr(col_idx), _ptr(col_cnt),
+                            _ptr(slash_idx), _ptr(slash_cnt), int(local_window), _ptr(out), out_dtype,
+                            _ptr(lse), _ptr(tiles), _ptr(ws), ws.numel() if ws is not None else 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_sparse_attn")
+    return out, lse, tiles
+
+
+def sa_dense_attn(q, k, v, scale: float = 0.0, out_dtype: int = SA_OUT_BF16, workspace=None,
+                  want_lse: bool = False):
+    """Dense causal attention.  Returns (out, lse or None)."""
+    lib = load_library()
+    sh = _shape_of(q, k, scale)
+    _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
+    _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
+    _check(v, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "v")
+    cs = sh.c()
+    need = int(lib.sa_workspace_bytes(SA_OP_DENSE_ATTN, ctypes.byref(cs), None))
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    out = torch.empty(q.shape, dtype=torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16, device=q.device)
+    lse = torch.empty(sh.n_bh, sh.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
+    st = lib.sa_dense_attn(ctypes.byref(cs), _ptr(q), _ptr(k), _ptr(v), _ptr(out), out_dtype, _ptr(lse),
+                           _ptr(ws), ws.numel() if ws is not None else 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_dense_attn")
+    return out, lse
+
+
+def sample_attention(q, k, v, n_sample_rows: int, alpha_c: float, alpha_s: float, local_window: int,
+                     scale: float = 0.0, out_dtype: int = SA_OUT_BF16):
+    """The whole path (Algorithm 1, chunk_n = 1): three library calls chained on
+    the current stream with no host synchronisation in between."""
+    sh = _shape_of(q, k, scale)
+    col, slash = sa_sample_scores(q, k, n_sample_rows, scale)
+    ci, cc, si, sc = sa_select_strips(col, slash, alpha_c, alpha_s, sh)
+    out, _, _ = sa_sparse_attn(q, k, v, ci, cc, si, sc, local_window, scale, out_dtype)
+    return out

@@ -1,0 +1,417 @@
+// Flash-style attention kernels for gfx950: dense causal attention (Eq. 1-2),
+// row log-sum-exp of the sampled queries (stage 1, pass 1) and attention under
+// the merged column / slash / window mask (Eq. 3, Algorithm 1 last step).
+//
+// One workgroup = 4 waves = 128 query rows of one head; each wave owns 32
+// queries.  Keys are visited in tiles of 64.  For every tile the wave forms
+// S^T = K Q^T (keys x queries) with 32x32x16 bf16 MFMAs, so that one lane holds
+// scores of ONE query (lane % 32) for 16 keys per 32-key half tile: the
+// row-wise online softmax is then in-lane arithmetic plus a single exchange
+// between lanes l and l^32.  The probabilities, rounded to bf16, are directly
+// the B operand of O^T += V^T P^T, so the accumulators (O^T, head_dim x
+// queries) again keep one query per lane and the rescale is a per-lane scalar.
+// K tiles live in LDS as [key][d]; V is read from a pre-transposed copy
+// (V^T, [d][key]) so both MFMA A operands are 16-byte LDS reads.
+#include "sa_device.h"
+#include "sa_kernels.h"
+
+namespace sa {
+
+namespace {
+
+constexpr int BQ = kFlashBQ;          // 128 query rows per workgroup
+constexpr int BK = kFlashBK;          // 64 keys per tile
+constexpr int NT = 256;
+constexpr int KROW_B = 272;           // bytes per K row in LDS (256 + 16 pad: conflict-free b128 reads)
+constexpr int VROW_B = 144;           // bytes per V^T row in LDS (128 + 16 pad)
+constexpr int KTILE_B = BK * KROW_B;
+constexpr int VTILE_B = kHeadDim * VROW_B;
+constexpr int IDX_B = BK * 4;
+constexpr int STAGE_B = KTILE_B + VTILE_B + IDX_B;
+
+enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
+
+struct Tile {
+  const uint16_t* k;    // first K row of the tile (row stride 128 elements)
+  const uint16_t* vt;   // &V^T[0][first key] (row stride vt_stride elements)
+  const int32_t* idx;   // key index of each of the 64 rows (TK_COLIDX) or null
+  int vt_stride;
+  int rows;             // valid K rows (rest read as zero)
+  int j0;               // first key index (contiguous tiles)
+  int kind;
+};
+
+}  // namespace
+
+// MODE: 0 dense causal, 1 row log-sum-exp only (no V), 2 strip-masked sparse.
+template <int MODE, bool OUT_F32>
+__global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr bool WITH_V = (MODE != 1);
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const int lane = tid & 63;
+  const int ql = lane & 31;   // query within the wave / row within a 32-row operand
+  const int hf = lane >> 5;   // which half of the contraction block this lane feeds
+
+  // ---- which (head, query tile) this workgroup owns ------------------------
+  int bh, a;
+  {
+    const int bid = blockIdx.x;
+    if (MODE == 2) {
+      // heads are sliced over the 8 XCDs (workgroups go round-robin to XCDs)
+      // so that the query tiles of one head, which stream the same gathered
+      // columns, run on the same L2; heavy (late) query tiles first.
+      if (P.n_bh >= 8) {
+        int xcd = bid & 7, slot = bid >> 3;
+        int per = (P.n_bh + 7) >> 3;
+        a = P.n_qtiles - 1 - slot / per;
+        bh = xcd + 8 * (slot % per);
+        if (bh >= P.n_bh || a < 0) return;
+      } else {
+        a = P.n_qtiles - 1 - bid / P.n_bh;
+        bh = bid % P.n_bh;
+        if (a < 0) return;
+      }
+    } else {
+      // a bundle = the query heads sharing one KV head at one query tile; the
+      // bundle's workgroups land on one XCD so the K/V stream is shared in L2.
+      int xcd = bid & 7, slot = bid >> 3;
+      int bl = slot / P.group, hg = slot % P.group;
+      int bundle = bl * 8 + xcd;
+      if (bundle >= P.n_qtiles * P.n_bkv) return;
+      a = P.n_qtiles - 1 - bundle / P.n_bkv;
+      int bkv = bundle % P.n_bkv;
+      bh = bkv * P.group + hg;
+    }
+  }
+  const int bkv = bh / P.group;
+  const int S = P.S;
+  const int i0 = P.q_row0 + a * BQ;                     // first query row of the workgroup
+  const int i_last_wg = min(i0 + BQ, P.q_row0 + P.n_qrows) - 1;  // last valid row
+  const int iw0 = i0 + 32 * wave;                        // first query row of the wave
+  const int i_me = iw0 + ql;                             // this lane's query row
+  const bool row_ok = i_me <= i_last_wg;
+
+  // ---- Q^T operand: 8 contraction steps of 16, resident in registers -------
+  bf16x8 qf[8];
+  {
+    const uint16_t* qrow = P.q + ((size_t)bh * S + (row_ok ? i_me : i_last_wg)) * kHeadDim;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(qrow + ks * 16 + hf * 8));
+  }
+
+  f32x16 o[4];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[mb][r] = 0.f;
+  float m_run = kNegBig;   // running max, in log2 units (score * scale * log2 e)
+  float l_run = 0.f;       // running sum of exp2 for this lane's keys
+  const float c2 = P.scale_log2;
+
+  // ---- tile schedule --------------------------------------------------------
+  const uint16_t* kbase = P.k + (size_t)bkv * S * kHeadDim;
+  const uint16_t* vtbase = WITH_V ? P.vt + (size_t)bkv * kHeadDim * P.S_pad : nullptr;
+  int n_col_tiles = 0, n_rng = 0;
+  const int32_t* cidx = nullptr;
+  const int32_t* dl = nullptr;
+  const uint32_t* cbits = nullptr;
+  const uint32_t* obits = nullptr;
+  const uint16_t* kc = nullptr;
+  const uint16_t* vct = nullptr;
+  const int a64 = i0 / BK;   // index of the 64-key tile that holds row i0 (i0 % 128 == 0 in MODE 2)
+  if (MODE == 2) {
+    cidx = P.col_idx_pad + (size_t)bh * P.cidx_stride;
+    int cnt = min(max(P.col_cnt[bh], 0), S);
+    // number of selected columns j <= last row of the tile (ascending list)
+    int lo = 0, hi = cnt;
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (cidx[mid] <= i_last_wg) lo = mid + 1; else hi = mid;
+    }
+    n_col_tiles = (lo + BK - 1) / BK;
+    dl = P.dlist + (size_t)bh * P.dlist_stride;
+    int dc = min(max(P.dcnt[bh], 0), P.dlist_stride);
+    // entries d of the ascending list with key tile a64 - d >= 0 ... d <= a64 + 1
+    lo = 0; hi = dc;
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (dl[mid] <= a64 + 1) lo = mid + 1; else hi = mid;
+    }
+    n_rng = lo;
+    cbits = P.col_bits + (size_t)bh * P.cb_words;
+    obits = P.off_bits + (size_t)bh * P.rb_words;
+    kc = P.kc + (size_t)bh * P.S_pad * kHeadDim;
+    vct = P.vct + (size_t)bh * kHeadDim * P.S_pad;
+  }
+  const int n_tiles = (MODE == 2) ? (n_col_tiles + n_rng) : (min(i_last_wg, S - 1) / BK + 1);
+
+  auto get_tile = [&](int t) -> Tile {
+    Tile T;
+    if (MODE == 2 && t < n_col_tiles) {
+      T.k = kc + (size_t)t * BK * kHeadDim;
+      T.vt = vct + t * BK;
+      T.vt_stride = P.S_pad;
+      T.idx = cidx + t * BK;
+      T.rows = BK;
+      T.j0 = 0;
+      T.kind = TK_COLIDX;
+    } else {
+      int j0;
+      if (MODE == 2) {
+        // d = (64-key tile of row i0 + 1) - key tile; walk from far to near
+        int d = dl[n_rng - 1 - (t - n_col_tiles)];
+        j0 = (a64 + 1 - d) * BK;
+        T.kind = TK_RANGE;
+      } else {
+        j0 = t * BK;
+        T.kind = (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
+      }
+      T.k = kbase + (size_t)j0 * kHeadDim;
+      T.vt = WITH_V ? vtbase + j0 : nullptr;
+      T.vt_stride = P.S_pad;
+      T.idx = nullptr;
+      T.rows = min(BK, S - j0);
+      T.j0 = j0;
+    }
+    return T;
+  };
+
+  // global -> registers -> LDS staging of one tile (K rows, V^T rows, key indices).
+  // Thread t moves 16-byte chunks t, t+256, t+512, t+768 of the K tile (16 chunks per
+  // row) and of the V^T tile (8 chunks per row).  Named registers, not arrays, so
+  // the prefetch never lands in scratch memory.
+  uint4 pk0, pk1, pk2, pk3, pv0, pv1, pv2, pv3;
+  pk0 = pk1 = pk2 = pk3 = pv0 = pv1 = pv2 = pv3 = make_uint4(0u, 0u, 0u, 0u);
+  int32_t pfi = 0;
+  const int krow_t = tid >> 4, kcol_t = tid & 15;     // + 16 rows per step
+  const int vrow_t = tid >> 3, vcol_t = tid & 7;      // + 32 rows per step
+  auto ld_k = [&](const Tile& t, int n) -> uint4 {
+    int row = krow_t + 16 * n;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (row < t.rows) v = *reinterpret_cast<const uint4*>(t.k + (size_t)row * kHeadDim + kcol_t * 8);
+    return v;
+  };
+  auto ld_v = [&](const Tile& t, int n) -> uint4 {
+    int drow = vrow_t + 32 * n;
+    return *reinterpret_cast<const uint4*>(t.vt + (size_t)drow * t.vt_stride + vcol_t * 8);
+  };
+  auto tile_load = [&](const Tile& t) {
+    pk0 = ld_k(t, 0); pk1 = ld_k(t, 1); pk2 = ld_k(t, 2); pk3 = ld_k(t, 3);
+    if (WITH_V) { pv0 = ld_v(t, 0); pv1 = ld_v(t, 1); pv2 = ld_v(t, 2); pv3 = ld_v(t, 3); }
+    if (MODE == 2) pfi = (t.idx != nullptr && tid < BK) ? t.idx[tid] : 0;
+  };
+  auto st_k = [&](char* stage, int n, uint4 v) {
+    *reinterpret_cast<uint4*>(stage + krow_slot(krow_t + 16 * n) * KROW_B + kcol_t * 16) = v;
+  };
+  auto st_v = [&](char* stage, int n, uint4 v) {
+    *reinterpret_cast<uint4*>(stage + KTILE_B + (vrow_t + 32 * n) * VROW_B + vcol_t * 16) = v;
+  };
+  auto tile_store = [&](char* stage, bool with_idx) {
+    st_k(stage, 0, pk0); st_k(stage, 1, pk1); st_k(stage, 2, pk2); st_k(stage, 3, pk3);
+    if (WITH_V) { st_v(stage, 0, pv0); st_v(stage, 1, pv1); st_v(stage, 2, pv2); st_v(stage, 3, pv3); }
+    if (MODE == 2 && with_idx && tid < BK) reinterpret_cast<int32_t*>(stage + KTILE_B + VTILE_B)[tid] = pfi;
+  };
+
+  unsigned long long tiles_done = 0;
+  if (n_tiles > 0) {
+    Tile T0 = get_tile(0);
+    tile_load(T0);
+    tile_store(smem, T0.kind == TK_COLIDX);
+  }
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    char* stage = smem + (t & 1) * STAGE_B;
+    Tile T = get_tile(t);
+    Tile Tn;
+    const bool have_next = (t + 1 < n_tiles);
+    if (have_next) {
+      Tn = get_tile(t + 1);
+      tile_load(Tn);
+    }
+
+    bool skip = false;
+    if (MODE == 2 && T.kind == TK_RANGE) {
+      // every key of the tile already belongs to a selected column: the
+      // column pass has covered it, nothing is left for the range pass
+      uint32_t w0 = cbits[T.j0 >> 5], w1 = cbits[(T.j0 >> 5) + 1];
+      skip = ((w0 & w1) == 0xFFFFFFFFu) || (T.rows <= 0);   // or the tile lies past the sequence end
+    }
+
+    if (!skip) {
+      ++tiles_done;
+      // ---- S^T = K Q^T for the two 32-key halves ----------------------------
+      f32x16 s[2];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
+        const char* kp = stage + (32 * sb + ql) * KROW_B + hf * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          bf16x8 kf = as_bf16x8(*reinterpret_cast<const uint4*>(kp + ks * 32));
+          s[sb] = mfma_32x32x16(kf, qf[ks], s[sb]);
+        }
+      }
+      // element r of s[sb] is key  j0 + 32*sb + 16*(r/8) + 8*hf + r%8  vs query i_me
+
+      // ---- mask ---------------------------------------------------------------
+      const float ninf = -__builtin_inff();
+      if (T.kind == TK_CAUSAL) {
+        if (T.j0 + BK - 1 > iw0) {
+#pragma unroll
+          for (int sb = 0; sb < 2; ++sb) {
+            int tl = i_me - (T.j0 + 32 * sb + 8 * hf);   // keep bit b iff b <= tl
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              int b = 16 * (r >> 3) + (r & 7);
+              s[sb][r] = (b <= tl) ? s[sb][r] : ninf;
+            }
+          }
+        }
+      } else if (MODE == 2 && T.kind == TK_COLIDX) {
+        const int32_t* il = reinterpret_cast<const int32_t*>(stage + KTILE_B + VTILE_B);
+        if (il[BK - 1] > iw0) {
+#pragma unroll
+          for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+              const int4* ip = reinterpret_cast<const int4*>(il + 32 * sb + 16 * u + 8 * hf);
+              int4 x0 = ip[0], x1 = ip[1];
+              int jj[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                s[sb][8 * u + e] = (jj[e] <= i_me) ? s[sb][8 * u + e] : ninf;
+            }
+        }
+      } else if (MODE == 2 && T.kind == TK_RANGE) {
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+          int tl = i_me - (T.j0 + 32 * sb + 8 * hf);
+          int x0 = P.off_max - tl;                       // >= 0 by construction of the bitmap
+          uint32_t lo = obits[x0 >> 5], hi = obits[(x0 >> 5) + 1];
+          uint32_t ow = __builtin_amdgcn_alignbit(hi, lo, x0 & 31);  // bit b <-> offset tl - b
+          uint32_t cw = cbits[(T.j0 >> 5) + sb] >> (8 * hf);         // bit 16u+e <-> key is a selected column
+          uint32_t km = ow & ~cw;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            int b = 16 * (r >> 3) + (r & 7);
+            s[sb][r] = ((km >> b) & 1u) ? s[sb][r] : ninf;
+          }
+        }
+      }
+
+      // ---- online softmax (one query per lane) -------------------------------
+      float mx = s[0][0];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+      mx = fmaxf(mx, swap_half(mx));
+      float m_new = fmaxf(m_run, mx * c2);
+      float alpha = fast_exp2(m_run - m_new);
+      m_run = m_new;
+      float rs = 0.f;
+      uint32_t pk[2][8];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+        float p[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_new));
+          rs += p[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) pk[sb][r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
+      }
+      l_run = fmaf(l_run, alpha, rs);
+
+      if (WITH_V) {
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+          for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
+        }
+        // ---- O^T += V^T P^T ---------------------------------------------------
+        const char* vp = stage + KTILE_B + ql * VROW_B + hf * 16;
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            uint4 pw = {pk[sb][4 * u], pk[sb][4 * u + 1], pk[sb][4 * u + 2], pk[sb][4 * u + 3]};
+            bf16x8 pb = as_bf16x8(pw);
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+              bf16x8 vf = as_bf16x8(*reinterpret_cast<const uint4*>(vp + mb * 32 * VROW_B + (32 * sb + 16 * u) * 2));
+              o[mb] = mfma_32x32x16(vf, pb, o[mb]);
+            }
+          }
+      }
+    }
+
+    if (have_next)
+      tile_store(smem + ((t + 1) & 1) * STAGE_B, Tn.kind == TK_COLIDX);
+    __syncthreads();
+  }
+
+  // ---- epilogue -------------------------------------------------------------
+  float l_tot = l_run + swap_half(l_run);
+  if (MODE == 2 && P.tiles != nullptr && tid == 0) atomicAdd(P.tiles + bh, tiles_done);
+  if (!row_ok) return;
+  if (P.lse != nullptr && hf == 0) {
+    size_t at = (MODE == 1) ? ((size_t)bh * P.n_qrows + (i_me - P.q_row0)) : ((size_t)bh * S + i_me);
+    P.lse[at] = m_run * kLn2 + __logf(l_tot);
+  }
+  if (WITH_V) {
+    float inv = 1.0f / l_tot;
+    size_t rowoff = ((size_t)bh * S + i_me) * kHeadDim;
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        int d = 32 * mb + 8 * g + 4 * hf;
+        float x0 = o[mb][4 * g] * inv, x1 = o[mb][4 * g + 1] * inv;
+        float x2 = o[mb][4 * g + 2] * inv, x3 = o[mb][4 * g + 3] * inv;
+        if (OUT_F32) {
+          float4 v4 = {x0, x1, x2, x3};
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(P.out) + rowoff + d) = v4;
+        } else {
+          uint2 v2 = {pack_bf16x2(x0, x1), pack_bf16x2(x2, x3)};
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(P.out) + rowoff + d) = v2;
+        }
+      }
+  }
+}
+
+template <int MODE, bool OUT_F32>
+static hipError_t launch_one(const FlashParams& P, int grid, hipStream_t st) {
+  size_t shmem = 2 * STAGE_B;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kernel<MODE, OUT_F32>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((flash_kernel<MODE, OUT_F32>), dim3(grid), dim3(NT), shmem, st, P);
+  return hipGetLastError();
+}
+
+hipError_t launch_flash(int mode, bool out_f32, const FlashParams& P, hipStream_t st) {
+  int grid;
+  if (mode == 2) {
+    grid = (P.n_bh >= 8) ? 8 * P.n_qtiles * ((P.n_bh + 7) / 8) : P.n_qtiles * P.n_bh;
+  } else {
+    int bundles = P.n_qtiles * P.n_bkv;
+    grid = ((bundles + 7) / 8) * 8 * P.group;
+  }
+  if (grid <= 0) return hipSuccess;
+  switch (mode) {
+    case 0: return out_f32 ? launch_one<0, true>(P, grid, st) : launch_one<0, false>(P, grid, st);
+    case 1: return launch_one<1, false>(P, grid, st);
+    default: return out_f32 ? launch_one<2, true>(P, grid, st) : launch_one<2, false>(P, grid, st);
+  }
+}
+
+}  // namespace sa

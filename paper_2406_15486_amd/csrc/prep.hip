@@ -1,0 +1,167 @@
+// Small data-movement kernels around the attention kernels:
+//  - gather_transpose: V -> V^T (so the PV product reads 16-byte MFMA operands)
+//    and, for the strip-masked path, K/V rows gathered by selected column index
+//    into compact per-head arrays (Algorithm 1, merge_index: column strips);
+//  - mask_prep: the selected columns and offsets (plus the local window) as
+//    bitmaps, and the list of 64-key tile diagonals that hold at least one kept
+//    offset (Algorithm 1, merge_index: slash strips extended over the matrix).
+#include "sa_device.h"
+#include "sa_kernels.h"
+
+namespace sa {
+
+namespace {
+
+constexpr int GT_ROW_B = 260;   // bytes per gathered row in LDS (256 + 4 pad)
+
+__global__ __launch_bounds__(256) void gather_transpose_kernel(GatherParams P) {
+  __shared__ __attribute__((aligned(16))) char tile[64 * GT_ROW_B];
+  const int g = blockIdx.y;
+  const int c0 = blockIdx.x * 64;
+  const int cnt = P.cnt ? min(max(P.cnt[g], 0), P.S) : P.S;
+  const int tid = threadIdx.x;
+  if (P.idx_pad != nullptr) {
+    // padded copy of the index list: INT_MAX marks "no column"
+    if (tid < 64) {
+      int c = c0 + tid;
+      if (c < P.idx_pad_stride)
+        P.idx_pad[(size_t)g * P.idx_pad_stride + c] = (c < cnt) ? P.idx[(size_t)g * P.idx_stride + c] : 0x7FFFFFFF;
+    }
+  }
+  if (c0 >= ((cnt + 63) & ~63)) return;   // nothing reads beyond the last partial tile
+  const uint16_t* src = P.src + (size_t)(g / P.group) * P.S * kHeadDim;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    int c = tid + 256 * n;
+    int row = c >> 4, col = c & 15;
+    int cc = c0 + row;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (cc < cnt) {
+      int j = P.idx ? P.idx[(size_t)g * P.idx_stride + cc] : cc;
+      j = min(max(j, 0), P.S - 1);   // a malformed list must not read out of bounds
+      v = *reinterpret_cast<const uint4*>(src + (size_t)j * kHeadDim + col * 8);
+    }
+    if (P.out_rows != nullptr)
+      *reinterpret_cast<uint4*>(P.out_rows + ((size_t)g * P.C_pad + cc) * kHeadDim + col * 8) = v;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(tile + row * GT_ROW_B + col * 16);
+    dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+  }
+  if (P.out_t == nullptr) return;   // rows-only gather
+  __syncthreads();
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    int c = tid + 256 * n;
+    int drow = c >> 3, kc = c & 7;
+    uint16_t e[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+      e[x] = *reinterpret_cast<const uint16_t*>(tile + (8 * kc + x) * GT_ROW_B + drow * 2);
+    uint4 v;
+    v.x = e[0] | ((uint32_t)e[1] << 16);
+    v.y = e[2] | ((uint32_t)e[3] << 16);
+    v.z = e[4] | ((uint32_t)e[5] << 16);
+    v.w = e[6] | ((uint32_t)e[7] << 16);
+    *reinterpret_cast<uint4*>(P.out_t + ((size_t)g * kHeadDim + drow) * P.C_pad + c0 + 8 * kc) = v;
+  }
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+
+__global__ __launch_bounds__(256) void set_bits_kernel(MaskPrepParams P) {
+  const int h = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  uint32_t* cb = P.col_bits + (size_t)h * P.cb_words;
+  uint32_t* ob = P.off_bits + (size_t)h * P.rb_words;
+  if (c < P.S && c < P.col_cnt[h]) {
+    int j = P.col_idx[(size_t)h * P.S + c];
+    if (j >= 0 && j < P.S) atomicOr(cb + (j >> 5), 1u << (j & 31));
+  }
+  if (c < P.S && c < P.slash_cnt[h]) {
+    int o = P.slash_idx[(size_t)h * P.S + c];
+    if (o >= 0 && o < P.S) {
+      int x = P.off_max - o;
+      atomicOr(ob + (x >> 5), 1u << (x & 31));
+    }
+  }
+  if (c < P.window && c < P.S) {
+    int x = P.off_max - c;
+    atomicOr(ob + (x >> 5), 1u << (x & 31));
+  }
+}
+
+// any kept offset in [lo, hi] (0 <= lo <= hi)?  offset o sits at bit off_max - o
+__device__ bool any_offset(const uint32_t* ob, int off_max, int lo, int hi) {
+  int x_lo = off_max - hi, x_hi = off_max - lo;
+  for (int w = x_lo >> 5; w <= (x_hi >> 5); ++w) {
+    uint32_t m = 0xFFFFFFFFu;
+    if (w == (x_lo >> 5)) m &= 0xFFFFFFFFu << (x_lo & 31);
+    if (w == (x_hi >> 5)) m &= 0xFFFFFFFFu >> (31 - (x_hi & 31));
+    if (ob[w] & m) return true;
+  }
+  return false;
+}
+
+// Tile diagonal d pairs the 128-row query tile starting at row i0 with the
+// 64-key tile starting at key i0 + 64 - 64 d: it spans offsets
+// [64 d - 127, 64 d + 63].  dlist = ascending d with at least one kept offset.
+__global__ __launch_bounds__(256) void dlist_kernel(MaskPrepParams P) {
+  __shared__ int wave_cnt[4];
+  __shared__ int base;
+  const int h = blockIdx.x;
+  const uint32_t* ob = P.off_bits + (size_t)h * P.rb_words;
+  int32_t* dl = P.dlist + (size_t)h * P.dlist_stride;
+  const int nd = (P.S + 63) / 64 + 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) base = 0;
+  __syncthreads();
+  for (int d0 = 0; d0 < nd; d0 += 256) {
+    int d = d0 + tid;
+    bool f = false;
+    if (d < nd) {
+      int lo = max(0, 64 * d - 127), hi = min(P.S - 1, 64 * d + 63);
+      f = (lo <= hi) && any_offset(ob, P.off_max, lo, hi);
+    }
+    unsigned long long b = __ballot(f);
+    if (lane == 0) wave_cnt[wave] = __popcll(b);
+    __syncthreads();
+    int pre = base;
+    for (int w = 0; w < wave; ++w) pre += wave_cnt[w];
+    if (f) dl[pre + __popcll(b & ((1ull << lane) - 1ull))] = d;
+    __syncthreads();
+    if (tid == 0) base += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    __syncthreads();
+  }
+  if (tid == 0) P.dcnt[h] = base;
+}
+
+}  // namespace
+
+hipError_t launch_gather_transpose(const GatherParams& P, hipStream_t st) {
+  dim3 grid(P.C_pad / 64, P.n_out);
+  if (grid.x == 0 || grid.y == 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_transpose_kernel, grid, dim3(256), 0, st, P);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks), dim3(256), 0, st, p, n, v);
+  return hipGetLastError();
+}
+
+hipError_t launch_mask_prep(const MaskPrepParams& P, hipStream_t st) {
+  size_t ncb = (size_t)P.n_bh * P.cb_words, nob = (size_t)P.n_bh * P.rb_words;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, P.col_bits, ncb, 0u);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, P.off_bits, nob, 0u);
+  dim3 grid((P.S + 255) / 256, P.n_bh);
+  hipLaunchKernelGGL(set_bits_kernel, grid, dim3(256), 0, st, P);
+  hipLaunchKernelGGL(dlist_kernel, dim3(P.n_bh), dim3(256), 0, st, P);
+  return hipGetLastError();
+}
+
+}  // namespace sa

@@ -1,0 +1,312 @@
+// C ABI of the library: host-side argument validation, workspace carving and
+// kernel launches.  Every check runs before the first launch, so error paths
+// need no GPU.  Declarations and contracts: include/sa.h.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/sa.h"
+#include "sa_kernels.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Dims {
+  int S, S_pad, n_bh, n_bkv, group;
+  float scale;
+};
+
+sa_status check_shape(const sa_shape* s, Dims* d) {
+  if (s == nullptr) return SA_ERR_INVALID_ARG;
+  if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->seq_len < 1) return SA_ERR_INVALID_ARG;
+  if (s->n_q_heads % s->n_kv_heads != 0) return SA_ERR_INVALID_ARG;
+  if (!(s->softmax_scale >= 0.0f) || !isfinite(s->softmax_scale)) return SA_ERR_INVALID_ARG;
+  if (s->head_dim != sa::kHeadDim) return SA_ERR_UNSUPPORTED;
+  if (s->causal != 1) return SA_ERR_UNSUPPORTED;
+  if ((long long)s->batch * s->n_q_heads > 65535) return SA_ERR_UNSUPPORTED;
+  if (s->seq_len > (1 << 30)) return SA_ERR_UNSUPPORTED;
+  d->S = s->seq_len;
+  d->S_pad = (s->seq_len + 127) / 128 * 128;
+  d->n_bh = s->batch * s->n_q_heads;
+  d->n_bkv = s->batch * s->n_kv_heads;
+  d->group = s->n_q_heads / s->n_kv_heads;
+  d->scale = (s->softmax_scale == 0.0f) ? 1.0f / sqrtf((float)s->head_dim) : s->softmax_scale;
+  return SA_OK;
+}
+
+sa_status check_sampling(const sa_sampling* sm, const Dims& d) {
+  if (sm == nullptr) return SA_ERR_INVALID_ARG;
+  if (sm->n_sample_rows < 1 || sm->n_sample_rows > d.S) return SA_ERR_INVALID_ARG;
+  if (sm->n_chunks < 1 || sm->granularity < 1) return SA_ERR_INVALID_ARG;
+  if (sm->n_chunks != 1 || sm->granularity != 1) return SA_ERR_UNSUPPORTED;
+  if (sm->n_sample_rows % 32 != 0 && sm->n_sample_rows != d.S) return SA_ERR_INVALID_ARG;
+  return SA_OK;
+}
+
+sa_status check_ws(const void* ws, size_t have, size_t need) {
+  if (need == 0) return SA_OK;
+  if (ws == nullptr || have < need) return SA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % kAlign != 0) return SA_ERR_WORKSPACE;
+  return SA_OK;
+}
+
+// ---- workspace layouts --------------------------------------------------------
+struct SampleWs { size_t lse, partial, total; };
+SampleWs sample_ws(const Dims& d, int n_s) {
+  SampleWs w;
+  size_t at = 0;
+  w.lse = at;     at += align_up((size_t)d.n_bh * n_s * sizeof(float));
+  w.partial = at; at += align_up(sa::score_partial_floats(d.S, n_s, d.n_bh) * sizeof(float));
+  w.total = at;
+  return w;
+}
+
+struct SparseWs {
+  size_t vt, kc, vct, cidx, cbits, obits, dlist, dcnt, total;
+  int cb_words, rb_words, dlist_stride, off_max;
+};
+SparseWs sparse_ws(const Dims& d) {
+  SparseWs w;
+  w.cb_words = d.S_pad / 32 + 2;
+  w.rb_words = d.S_pad / 32 + 8;
+  w.dlist_stride = d.S_pad / 64 + 2;
+  w.off_max = d.S_pad - 1;
+  size_t at = 0;
+  w.vt = at;    at += align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2);
+  w.kc = at;    at += align_up((size_t)d.n_bh * d.S_pad * sa::kHeadDim * 2);
+  w.vct = at;   at += align_up((size_t)d.n_bh * sa::kHeadDim * d.S_pad * 2);
+  w.cidx = at;  at += align_up((size_t)d.n_bh * d.S_pad * 4);
+  w.cbits = at; at += align_up((size_t)d.n_bh * w.cb_words * 4);
+  w.obits = at; at += align_up((size_t)d.n_bh * w.rb_words * 4);
+  w.dlist = at; at += align_up((size_t)d.n_bh * w.dlist_stride * 4);
+  w.dcnt = at;  at += align_up((size_t)d.n_bh * 4);
+  w.total = at;
+  return w;
+}
+
+size_t dense_ws(const Dims& d) { return align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2); }
+
+inline sa_status dev(hipError_t e) { return e == hipSuccess ? SA_OK : SA_ERR_DEVICE; }
+
+sa::FlashParams base_flash(const Dims& d, const void* q, const void* k) {
+  sa::FlashParams P;
+  memset(&P, 0, sizeof(P));
+  P.q = static_cast<const uint16_t*>(q);
+  P.k = static_cast<const uint16_t*>(k);
+  P.S = d.S; P.S_pad = d.S_pad;
+  P.n_bh = d.n_bh; P.n_bkv = d.n_bkv; P.group = d.group;
+  P.scale_log2 = d.scale * 1.4426950408889634f;
+  P.n_qtiles = (d.S + sa::kFlashBQ - 1) / sa::kFlashBQ;
+  P.q_row0 = 0; P.n_qrows = d.S;
+  return P;
+}
+
+hipError_t transpose_v(const Dims& d, const void* v, uint16_t* vt, hipStream_t st) {
+  sa::GatherParams G;
+  memset(&G, 0, sizeof(G));
+  G.src = static_cast<const uint16_t*>(v);
+  G.out_t = vt;
+  G.n_out = d.n_bkv; G.group = 1;
+  G.S = d.S; G.C_pad = d.S_pad;
+  return sa::launch_gather_transpose(G, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sa_workspace_bytes(int op, const sa_shape* shape, const sa_sampling* sampling) {
+  Dims d;
+  if (check_shape(shape, &d) != SA_OK) return 0;
+  switch (op) {
+    case SA_OP_SAMPLE_SCORES:
+      if (check_sampling(sampling, d) != SA_OK) return 0;
+      return sample_ws(d, sampling->n_sample_rows).total;
+    case SA_OP_SELECT_STRIPS: return 0;
+    case SA_OP_SPARSE_ATTN: return sparse_ws(d).total;
+    case SA_OP_DENSE_ATTN: return dense_ws(d);
+    default: return 0;
+  }
+}
+
+int32_t sa_rows_from_ratio(int32_t seq_len, float ratio) {
+  if (seq_len < 1 || !(ratio > 0.0f)) return 0;
+  double blocks = ceil((double)ratio * (double)seq_len / 64.0 - 1e-9);
+  if (blocks < 1.0) blocks = 1.0;
+  double n = 64.0 * blocks;
+  return (n > (double)seq_len) ? seq_len : (int32_t)n;
+}
+
+sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
+                           const void* q, const void* k,
+                           float* col_scores, float* slash_scores, float* row_lse,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  Dims d;
+  sa_status s = check_shape(shape, &d);
+  if (s != SA_OK) return s;
+  s = check_sampling(sampling, d);
+  if (s != SA_OK) return s;
+  if (q == nullptr || k == nullptr || col_scores == nullptr || slash_scores == nullptr) return SA_ERR_INVALID_ARG;
+  const int n_s = sampling->n_sample_rows;
+  SampleWs w = sample_ws(d, n_s);
+  s = check_ws(workspace, workspace_bytes, w.total);
+  if (s != SA_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* lse = row_lse ? row_lse : reinterpret_cast<float*>(ws + w.lse);
+
+  // pass 1: log-sum-exp of every sampled row (flash sweep without V)
+  sa::FlashParams P = base_flash(d, q, k);
+  P.lse = lse;
+  P.q_row0 = d.S - n_s;
+  P.n_qrows = n_s;
+  P.n_qtiles = (n_s + sa::kFlashBQ - 1) / sa::kFlashBQ;
+  s = dev(sa::launch_flash(1, false, P, st));
+  if (s != SA_OK) return s;
+
+  // pass 2: recompute the probabilities and accumulate columns and diagonals
+  sa::ScoreParams C;
+  memset(&C, 0, sizeof(C));
+  C.q = static_cast<const uint16_t*>(q);
+  C.k = static_cast<const uint16_t*>(k);
+  C.lse = lse;
+  C.col = col_scores; C.slash = slash_scores;
+  C.partial = reinterpret_cast<float*>(ws + w.partial);
+  C.S = d.S; C.n_s = n_s; C.n_bh = d.n_bh; C.n_bkv = d.n_bkv; C.group = d.group;
+  C.scale_log2 = P.scale_log2;
+  return dev(sa::launch_score_accumulate(C, st));
+}
+
+sa_status sa_select_strips(const sa_shape* shape,
+                           const float* col_scores, const float* slash_scores,
+                           float alpha_c, float alpha_s,
+                           int32_t* col_idx, int32_t* col_cnt,
+                           int32_t* slash_idx, int32_t* slash_cnt,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  Dims d;
+  sa_status s = check_shape(shape, &d);
+  if (s != SA_OK) return s;
+  if (col_scores == nullptr || slash_scores == nullptr || col_idx == nullptr || col_cnt == nullptr ||
+      slash_idx == nullptr || slash_cnt == nullptr)
+    return SA_ERR_INVALID_ARG;
+  if (!(alpha_c >= 0.0f) || !(alpha_s >= 0.0f) || !isfinite(alpha_c) || !isfinite(alpha_s))
+    return SA_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  sa::SelectParams P;
+  P.n_prob = d.n_bh; P.S = d.S;
+  P.scores = col_scores; P.idx = col_idx; P.cnt = col_cnt; P.alpha = alpha_c;
+  s = dev(sa::launch_select(P, st));
+  if (s != SA_OK) return s;
+  P.scores = slash_scores; P.idx = slash_idx; P.cnt = slash_cnt; P.alpha = alpha_s;
+  return dev(sa::launch_select(P, st));
+}
+
+sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
+                         const int32_t* col_idx, const int32_t* col_cnt,
+                         const int32_t* slash_idx, const int32_t* slash_cnt,
+                         int32_t local_window,
+                         void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  Dims d;
+  sa_status s = check_shape(shape, &d);
+  if (s != SA_OK) return s;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || col_idx == nullptr ||
+      col_cnt == nullptr || slash_idx == nullptr || slash_cnt == nullptr)
+    return SA_ERR_INVALID_ARG;
+  if (local_window < 1) return SA_ERR_INVALID_ARG;
+  if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
+  SparseWs w = sparse_ws(d);
+  s = check_ws(workspace, workspace_bytes, w.total);
+  if (s != SA_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+
+  // merge_index, slash side: bitmaps of kept columns / offsets and touched tile diagonals
+  sa::MaskPrepParams M;
+  memset(&M, 0, sizeof(M));
+  M.col_idx = col_idx; M.col_cnt = col_cnt; M.slash_idx = slash_idx; M.slash_cnt = slash_cnt;
+  M.col_bits = reinterpret_cast<uint32_t*>(ws + w.cbits);
+  M.off_bits = reinterpret_cast<uint32_t*>(ws + w.obits);
+  M.dlist = reinterpret_cast<int32_t*>(ws + w.dlist);
+  M.dcnt = reinterpret_cast<int32_t*>(ws + w.dcnt);
+  M.n_bh = d.n_bh; M.S = d.S; M.window = local_window;
+  M.cb_words = w.cb_words; M.rb_words = w.rb_words; M.dlist_stride = w.dlist_stride; M.off_max = w.off_max;
+  s = dev(sa::launch_mask_prep(M, st));
+  if (s != SA_OK) return s;
+
+  // V^T for the contiguous (slash / window) tiles
+  s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
+  if (s != SA_OK) return s;
+
+  // merge_index, column side: compact K rows and V^T columns of the kept keys, per query head
+  sa::GatherParams G;
+  memset(&G, 0, sizeof(G));
+  G.idx = col_idx; G.cnt = col_cnt; G.idx_stride = d.S;
+  G.idx_pad = reinterpret_cast<int32_t*>(ws + w.cidx); G.idx_pad_stride = d.S_pad;
+  G.n_out = d.n_bh; G.group = d.group; G.S = d.S; G.C_pad = d.S_pad;
+  G.src = static_cast<const uint16_t*>(v);
+  G.out_t = reinterpret_cast<uint16_t*>(ws + w.vct);
+  s = dev(sa::launch_gather_transpose(G, st));
+  if (s != SA_OK) return s;
+  // K rows: gather only
+  G.src = static_cast<const uint16_t*>(k);
+  G.out_rows = reinterpret_cast<uint16_t*>(ws + w.kc);
+  G.out_t = nullptr;
+  G.idx_pad = nullptr;
+  s = dev(sa::launch_gather_transpose(G, st));
+  if (s != SA_OK) return s;
+
+  if (tiles != nullptr) {
+    s = dev(sa::launch_fill_u32(reinterpret_cast<uint32_t*>(tiles), 2 * (size_t)d.n_bh, 0u, st));
+    if (s != SA_OK) return s;
+  }
+  sa::FlashParams P = base_flash(d, q, k);
+  P.vt = reinterpret_cast<const uint16_t*>(ws + w.vt);
+  P.out = out; P.lse = out_lse;
+  P.kc = reinterpret_cast<const uint16_t*>(ws + w.kc);
+  P.vct = reinterpret_cast<const uint16_t*>(ws + w.vct);
+  P.col_idx_pad = reinterpret_cast<const int32_t*>(ws + w.cidx);
+  P.col_cnt = col_cnt;
+  P.col_bits = M.col_bits; P.off_bits = M.off_bits;
+  P.dlist = M.dlist; P.dcnt = M.dcnt;
+  P.tiles = reinterpret_cast<unsigned long long*>(tiles);
+  P.cidx_stride = d.S_pad; P.cb_words = w.cb_words; P.rb_words = w.rb_words;
+  P.dlist_stride = w.dlist_stride; P.off_max = w.off_max;
+  return dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
+}
+
+sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
+                        void* out, int out_dtype, float* out_lse,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  Dims d;
+  sa_status s = check_shape(shape, &d);
+  if (s != SA_OK) return s;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr) return SA_ERR_INVALID_ARG;
+  if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
+  s = check_ws(workspace, workspace_bytes, dense_ws(d));
+  if (s != SA_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint16_t* vt = static_cast<uint16_t*>(workspace);
+  s = dev(transpose_v(d, v, vt, st));
+  if (s != SA_OK) return s;
+  sa::FlashParams P = base_flash(d, q, k);
+  P.vt = vt; P.out = out; P.lse = out_lse;
+  return dev(sa::launch_flash(0, out_dtype == SA_OUT_F32, P, st));
+}
+
+const char* sa_status_string(int status) {
+  switch (status) {
+    case SA_OK: return "ok";
+    case SA_ERR_INVALID_ARG: return "invalid argument";
+    case SA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SA_ERR_DEVICE: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int sa_version(void) { return 100; }
+
+}  // extern "C"

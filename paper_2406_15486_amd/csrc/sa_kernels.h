@@ -1,0 +1,86 @@
+// Host-visible declarations of the kernel launchers (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sa {
+
+constexpr int kHeadDim = 128;  // the only supported head dimension
+constexpr int kFlashBQ = 128;  // query rows per workgroup of the flash kernels
+constexpr int kFlashBK = 64;   // keys per tile
+
+struct FlashParams {
+  const uint16_t* q;        // [n_bh, S, 128] bf16
+  const uint16_t* k;        // [n_bkv, S, 128] bf16
+  const uint16_t* vt;       // [n_bkv, 128, S_pad] bf16 (V transposed, zero padded)
+  void* out;                // [n_bh, S, 128] bf16 or fp32
+  float* lse;               // nullable
+  int S, S_pad;
+  int n_bh, n_bkv, group;   // batch*q-heads, batch*kv-heads, q heads per kv head
+  float scale_log2;         // softmax scale * log2(e)
+  int n_qtiles;             // 128-row query tiles to process
+  int q_row0, n_qrows;      // first query row and number of rows (sampled rows in mode 1)
+  // strip-masked mode only
+  const uint16_t* kc;           // [n_bh, S_pad, 128] K rows gathered by column index
+  const uint16_t* vct;          // [n_bh, 128, S_pad] V rows gathered and transposed
+  const int32_t* col_idx_pad;   // [n_bh, cidx_stride] ascending, padded with INT_MAX
+  const int32_t* col_cnt;       // [n_bh]
+  const uint32_t* col_bits;     // [n_bh, cb_words]  bit j: key j is a selected column
+  const uint32_t* off_bits;     // [n_bh, rb_words]  bit x: offset off_max - x is kept
+  const int32_t* dlist;         // [n_bh, dlist_stride] ascending touched tile-diagonals
+  const int32_t* dcnt;          // [n_bh]
+  unsigned long long* tiles;    // nullable [n_bh]
+  int cidx_stride, cb_words, rb_words, dlist_stride, off_max;
+};
+
+// mode 0: dense causal; 1: row log-sum-exp of rows [q_row0, q_row0+n_qrows); 2: strip mask
+hipError_t launch_flash(int mode, bool out_f32, const FlashParams& P, hipStream_t st);
+
+// out[g][d][c] = src[kv(g)][idx ? idx[g][c] : c][d] for c < cnt (zero beyond, up to C_pad);
+// optionally also rows_out[g][c][:] = src[kv(g)][idx[g][c]][:]
+struct GatherParams {
+  const uint16_t* src;      // [n_src, S, 128]
+  const int32_t* idx;       // nullable [n_out, idx_stride]
+  const int32_t* cnt;       // nullable [n_out]; null -> S
+  uint16_t* out_t;          // [n_out, 128, C_pad]
+  uint16_t* out_rows;       // nullable [n_out, C_pad, 128]
+  int32_t* idx_pad;         // nullable [n_out, idx_pad_stride]: copy of idx padded with INT_MAX
+  int n_out, group;         // source head of output g is g / group
+  int S, C_pad, idx_stride, idx_pad_stride;
+};
+hipError_t launch_gather_transpose(const GatherParams& P, hipStream_t st);
+
+struct MaskPrepParams {
+  const int32_t* col_idx; const int32_t* col_cnt;      // [n_bh, S], [n_bh]
+  const int32_t* slash_idx; const int32_t* slash_cnt;
+  uint32_t* col_bits; uint32_t* off_bits;              // zero-filled by the launcher
+  int32_t* dlist; int32_t* dcnt;
+  int n_bh, S, window, cb_words, rb_words, dlist_stride, off_max;
+};
+hipError_t launch_mask_prep(const MaskPrepParams& P, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st);
+
+struct ScoreParams {
+  const uint16_t* q; const uint16_t* k;
+  const float* lse;         // [n_bh, n_s] natural log
+  float* col;               // [n_bh, S]
+  float* slash;             // [n_bh, S]
+  float* partial;           // workspace for slash partial sums
+  int S, n_s, n_bh, n_bkv, group;
+  float scale_log2;
+  int n_kblocks, n_chunks, chunk_rows, win;   // win = floats per (key block, chunk) partial
+};
+hipError_t launch_score_accumulate(const ScoreParams& P, hipStream_t st);
+size_t score_partial_floats(int S, int n_s, int n_bh);
+void score_geometry(int S, int n_s, int* n_kblocks, int* n_chunks, int* chunk_rows, int* win);
+
+struct SelectParams {
+  const float* scores;      // [n_prob, S]
+  int32_t* idx;             // [n_prob, S]
+  int32_t* cnt;             // [n_prob]
+  int n_prob, S;
+  float alpha;
+};
+hipError_t launch_select(const SelectParams& P, hipStream_t st);
+
+}  // namespace sa
