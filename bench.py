@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the SampleAttention prefill hot path on one MI355X.
+
+One *step* = one pass of the whole path over one layer's attention inputs:
+sa_sample_scores -> sa_select_strips -> sa_sparse_attn, chained on one stream
+with the inputs already resident in HBM.  Prints ONE JSON line:
+
+  metric  sparse prefill attention ms/layer (the benchmark's metric) on the
+          workload named in config.workload (default: the S=128K ChatGLM3-6B-
+          shaped config, alpha = 0.95, literal generator constants)
+  roofline      the strip-masked flash kernel against the bf16 MFMA peak:
+                4*d*(computed 128x64 tiles) flop / mean kernel duration taken
+                from HIP events the library records around the launch, on the
+                launch stream, inside the timed region
+  cpu_baseline  the fp64 oracle timed on this host on a bounded sample of the
+                same workload, extrapolated linearly to one layer
+
+Everything else on the line (per-stage times, the in-library dense kernel,
+speedup, kept fractions, alpha sweep) is context.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+TILE_FLOP = 4 * 128 * 128 * 64   # QK^T + PV of one 128x64 score tile at d = 128
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def to_device(bits: np.ndarray):
+    import torch
+    t = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16)
+    return t[None].contiguous().cuda()
+
+
+def mask_density(S: int, cols: np.ndarray, offs: np.ndarray, window: int) -> float:
+    """Kept fraction of the causal triangle for one head (counting only)."""
+    off_keep = np.zeros(S, dtype=bool)
+    off_keep[offs] = True
+    off_keep[:window] = True
+    oo = np.nonzero(off_keep)[0]
+    n_col = int(np.sum(S - cols.astype(np.int64)))
+    n_off = int(np.sum(S - oo))
+    both = int(np.sum(np.searchsorted(oo, S - 1 - cols.astype(np.int64), side="right")))
+    return (n_col + n_off - both) / (S * (S + 1) / 2.0)
+
+
+def cpu_baseline(wl, x, alpha: float, budget_rows: int, attend_rows: int) -> dict:
+    """Oracle timing on a bounded sample, scaled to ms per layer."""
+    from oracle import sample_attention as O        # CPU-baseline leg only
+    from sa_inputs import bf16_bits_to_f32
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    S, n_s = wl.seq_len, wl.n_sample_rows
+    q = bf16_bits_to_f32(x["q"][0]).astype(np.float64)
+    k = bf16_bits_to_f32(x["k"][0]).astype(np.float64)
+    v = bf16_bits_to_f32(x["v"][0]).astype(np.float64)
+    rows1 = min(budget_rows, n_s)
+    t0 = time.perf_counter()
+    col, slash, _ = O.sample_scores(q, k, rows1)
+    t1 = time.perf_counter()
+    a32 = float(np.float32(alpha))
+    Ic, Is = O.select(col, a32), O.select(slash, a32)
+    t2 = time.perf_counter()
+    rows = np.linspace(0, S - 1, attend_rows).astype(np.int64)
+    O.masked_attn(q, k, v, Ic, Is, wl.window, rows=rows)
+    t3 = time.perf_counter()
+    per_head = (t1 - t0) * (n_s / rows1) + (t2 - t1) + (t3 - t2) * (S / attend_rows)
+    layer_ms = per_head * wl.n_q_heads * 1e3
+    return {
+        "value": layer_ms, "unit": "ms/layer", "cores": int(cores), "kind": "oracle",
+        "sample": (f"query head 0 of {wl.n_q_heads}: stage 1 on the last {rows1} of {n_s} sampled rows "
+                   f"({t1 - t0:.2f} s), selection on those scores ({t2 - t1:.2f} s), masked attention on "
+                   f"{attend_rows} of {S} rows ({t3 - t2:.2f} s); scaled linearly to all rows and heads"),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="glm128k")
+    ap.add_argument("--seq-len", type=int, default=0, help="override the workload's sequence length")
+    ap.add_argument("--alpha", type=float, default=0.95)
+    ap.add_argument("--structure-gain", type=float, default=1.0,
+                    help="multiply the planted sink gain / query bias (labelled variant workload)")
+    ap.add_argument("--dense-iters", type=int, default=2)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the alpha sweep")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=768)
+    ap.add_argument("--cpu-attend-rows", type=int, default=48)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2406_15486_amd as sa
+    from sa_inputs import CONFIGS, make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    sa.load_library()
+
+    wl = CONFIGS[args.workload]
+    if args.seq_len:
+        wl = wl.scaled(args.seq_len)
+    if args.structure_gain != 1.0:
+        wl = wl.with_structure_gain(args.structure_gain)
+    S, Hq, Hkv, n_s, w = wl.seq_len, wl.n_q_heads, wl.n_kv_heads, wl.n_sample_rows, wl.window
+    log(f"workload {wl.name}: S={S} Hq={Hq} Hkv={Hkv} n_s={n_s} window={w} alpha={args.alpha}")
+    t0 = time.perf_counter()
+    x = make_inputs(wl)
+    log(f"inputs generated on the host in {time.perf_counter() - t0:.1f} s")
+    q, k, v = to_device(x["q"]), to_device(x["k"]), to_device(x["v"])
+    shape = sa.Shape(1, Hq, Hkv, S)
+    plan = sa.SampleAttentionPlan(shape, n_s)
+    torch.cuda.synchronize()
+
+    # ---- timed region: K whole steps ----------------------------------------------
+    for _ in range(args.warmup):
+        plan.run(q, k, v, args.alpha, args.alpha, w)
+    torch.cuda.synchronize()
+    sa.sa_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        plan.run(q, k, v, args.alpha, args.alpha, w)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    stage = {name: sa.sa_profile_read(name) for name in
+             ("row_lse", "score_accum", "score_final", "select", "mask_prep", "sparse_flash")}
+    stage_ms = {n: (float(np.mean(vv)) if vv else None) for n, vv in stage.items()}
+    log(f"ms/step {ms_per_step:.3f}; stages {json.dumps(stage_ms)}")
+
+    tiles = plan.tiles.cpu().numpy().astype(np.int64)
+    flash_ms = stage_ms["sparse_flash"]
+    flop = float(tiles.sum()) * TILE_FLOP
+    achieved = flop / (flash_ms * 1e-3) / 1e12
+    dense_tiles = sum((min(128 * a + 127, S - 1) // 64 + 1) for a in range((S + 127) // 128)) * Hq
+    cc = plan.col_cnt.cpu().numpy()
+    sc = plan.slash_cnt.cpu().numpy()
+    ci = plan.col_idx[0, :int(cc[0])].cpu().numpy()
+    si = plan.slash_idx[0, :int(sc[0])].cpu().numpy()
+    density0 = mask_density(S, ci, si, w)
+
+    # ---- in-library dense kernel on the same inputs --------------------------------
+    dense_ms = None
+    if args.dense_iters > 0:
+        plan.dense(q, k, v)
+        torch.cuda.synchronize()
+        sa.sa_profile_enable(True)
+        for _ in range(args.dense_iters):
+            plan.dense(q, k, v)
+        torch.cuda.synchronize()
+        dk = sa.sa_profile_read("dense_flash")
+        dt = sa.sa_profile_read("transpose_v")
+        dense_ms = float(np.mean(dk)) + float(np.mean(dt))
+        dense_kernel_tflops = dense_tiles * TILE_FLOP / (float(np.mean(dk)) * 1e-3) / 1e12
+        log(f"dense kernel {np.mean(dk):.3f} ms (+{np.mean(dt):.3f} ms V^T) -> {dense_kernel_tflops:.1f} TFLOP/s")
+
+    # ---- alpha sweep (selection + attention only; stage 1 does not depend on alpha) --
+    sweep = []
+    if not args.no_sweep and len(wl.alphas) > 1:
+        plan.sample(q, k)
+        for a in wl.alphas:
+            plan.select(a, a)
+            plan.attend(q, k, v, w)          # warm
+            torch.cuda.synchronize()
+            sa.sa_profile_enable(True)
+            plan.select(a, a)
+            plan.attend(q, k, v, w)
+            torch.cuda.synchronize()
+            t_sel = float(np.mean(sa.sa_profile_read("select")))
+            t_prep = float(np.mean(sa.sa_profile_read("mask_prep")))
+            t_fl = float(np.mean(sa.sa_profile_read("sparse_flash")))
+            tl = plan.tiles.cpu().numpy().astype(np.int64)
+            stage1 = sum(stage_ms[n] for n in ("row_lse", "score_accum", "score_final"))
+            total = stage1 + t_sel + t_prep + t_fl
+            cca, sca = plan.col_cnt.cpu().numpy(), plan.slash_cnt.cpu().numpy()
+            d0 = mask_density(S, plan.col_idx[0, :int(cca[0])].cpu().numpy(),
+                              plan.slash_idx[0, :int(sca[0])].cpu().numpy(), w)
+            sweep.append({
+                "alpha": a, "ms_layer": total, "sparse_flash_ms": t_fl,
+                "computed_tile_fraction": float(tl.sum()) / dense_tiles,
+                "mask_density_head0": d0,
+                "mean_k_c": float(cca.mean()), "mean_k_s": float(sca.mean()),
+                "speedup_vs_dense": (dense_ms / total) if dense_ms else None,
+                "flash_tflops": float(tl.sum()) * TILE_FLOP / (t_fl * 1e-3) / 1e12,
+            })
+            log(f"alpha {a}: {json.dumps(sweep[-1])}")
+    sa.sa_profile_enable(False)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        t0 = time.perf_counter()
+        cpu = cpu_baseline(wl, x, args.alpha, args.cpu_rows, args.cpu_attend_rows)
+        log(f"cpu baseline took {time.perf_counter() - t0:.1f} s: {cpu['value']:.0f} ms/layer")
+
+    line = {
+        "metric": "sparse prefill attention ms/layer",
+        "value": ms_per_step,
+        "unit": "ms/layer",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: batch 1, {Hq} q heads / {Hkv} kv heads, d=128, S={S}, causal, bf16, "
+                        f"{wl.n_sinks} sinks + {wl.n_slash} slash offsets per kv head, alpha={args.alpha}, "
+                        f"sample rows={n_s}, window={w}",
+            "alpha": args.alpha, "seq_len": S, "n_sample_rows": n_s, "window": w,
+        },
+        "roofline": {
+            "kernel": "flash_kernel<strip-masked>", "bound": "mfma", "achieved": achieved,
+            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+            "traffic": None,
+            "flop_per_launch": flop, "kernel_ms": flash_ms,
+        },
+        "cpu_baseline": cpu,
+        "stage_ms": stage_ms,
+        "computed_tile_fraction": float(tiles.sum()) / dense_tiles,
+        "mask_density_head0": density0,
+        "mean_k_c": float(cc.mean()), "mean_k_s": float(sc.mean()),
+        "dense_ms": dense_ms,
+        "dense_kernel_tflops": dense_kernel_tflops if dense_ms else None,
+        "speedup_vs_dense": (dense_ms / ms_per_step) if dense_ms else None,
+        "alpha_sweep": sweep,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

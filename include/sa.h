@@ -157,6 +157,31 @@ sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, con
                         void* out, int out_dtype, float* out_lse,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid (no part of the method).  While enabled, the library
+ * records a HIP event pair on the caller's stream around each of its kernels
+ * (or kernel groups), into a ring of SA_PROFILE_SLOTS slots per kernel id.
+ * sa_profile_read waits for the recorded events and copies the durations, in
+ * milliseconds and oldest first, of up to `cap` launches recorded since the
+ * last sa_profile_enable(1) into `ms` (a HOST array); it returns the number
+ * written, or -1 for a bad argument.  Event records do not synchronise.
+ * Not thread-safe.
+ */
+typedef enum {
+  SA_K_ROW_LSE = 0,        /* stage 1 pass 1: flash sweep giving row log-sum-exp   */
+  SA_K_SCORE_ACCUM = 1,    /* stage 1 pass 2: column / slash accumulation          */
+  SA_K_SCORE_FINAL = 2,    /* stage 1: fixed-order sum of the partials             */
+  SA_K_SELECT = 3,         /* stage 2: both selection launches                     */
+  SA_K_MASK_PREP = 4,      /* merge: bitmaps, tile-diagonal list, V^T, K/V gathers */
+  SA_K_SPARSE_FLASH = 5,   /* strip-masked flash attention kernel                  */
+  SA_K_DENSE_FLASH = 6,    /* dense flash attention kernel                         */
+  SA_K_TRANSPOSE_V = 7,    /* V -> V^T of the dense path                           */
+  SA_K_COUNT = 8
+} sa_kernel_id;
+#define SA_PROFILE_SLOTS 64
+sa_status sa_profile_enable(int enable);
+int sa_profile_read(int kernel, float* ms, int cap);
+
 const char* sa_status_string(int status);
 int sa_version(void);
 

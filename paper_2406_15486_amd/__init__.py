@@ -8,11 +8,15 @@ stream, nothing else.
 from .binding import (  # noqa: F401
     SA_OUT_BF16,
     SA_OUT_F32,
+    SA_KERNELS,
     SaError,
+    SampleAttentionPlan,
     Shape,
     lib_path,
     load_library,
     sa_dense_attn,
+    sa_profile_enable,
+    sa_profile_read,
     sa_rows_from_ratio,
     sa_sample_scores,
     sa_select_strips,

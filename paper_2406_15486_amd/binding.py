@@ -94,6 +94,10 @@ def load_library() -> ctypes.CDLL:
     lib.sa_dense_attn.restype = ctypes.c_int
     lib.sa_dense_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p,
                                   vp, ctypes.c_size_t, vp]
+    lib.sa_profile_enable.restype = ctypes.c_int
+    lib.sa_profile_enable.argtypes = [ctypes.c_int]
+    lib.sa_profile_read.restype = ctypes.c_int
+    lib.sa_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
     lib.sa_status_string.restype = ctypes.c_char_p
     lib.sa_status_string.argtypes = [ctypes.c_int]
     lib.sa_version.restype = ctypes.c_int
@@ -225,6 +229,84 @@ def sa_dense_attn(q, k, v, scale: float = 0.0, out_dtype: int = SA_OUT_BF16, wor
     if st != 0:
         raise SaError(st, "sa_dense_attn")
     return out, lse
+
+
+SA_KERNELS = {"row_lse": 0, "score_accum": 1, "score_final": 2, "select": 3, "mask_prep": 4,
+              "sparse_flash": 5, "dense_flash": 6, "transpose_v": 7}
+
+
+def sa_profile_enable(enable: bool) -> None:
+    st = load_library().sa_profile_enable(1 if enable else 0)
+    if st != 0:
+        raise SaError(st, "sa_profile_enable")
+
+
+def sa_profile_read(kernel: str):
+    """Durations (ms, oldest first) of the recorded launches of one kernel."""
+    buf = (ctypes.c_float * 64)()
+    n = load_library().sa_profile_read(SA_KERNELS[kernel], buf, 64)
+    if n < 0:
+        raise RuntimeError("sa_profile_read failed (profiling never enabled?)")
+    return [float(buf[i]) for i in range(n)]
+
+
+class SampleAttentionPlan:
+    """Buffers for repeated calls on one shape: workspaces, score vectors, index
+    lists and the output are allocated once, so a step is three library calls
+    and nothing else (no allocation, no host synchronisation)."""
+
+    def __init__(self, shape: Shape, n_sample_rows: int, device="cuda", out_dtype: int = SA_OUT_BF16):
+        lib = load_library()
+        self.lib, self.shape, self.n_s, self.out_dtype = lib, shape, n_sample_rows, out_dtype
+        self.cs = shape.c()
+        self.sm = _CSampling(n_sample_rows, 1, 1)
+        need = max(int(lib.sa_workspace_bytes(op, ctypes.byref(self.cs), ctypes.byref(self.sm)))
+                   for op in (SA_OP_SAMPLE_SCORES, SA_OP_SPARSE_ATTN, SA_OP_DENSE_ATTN))
+        if need == 0:
+            raise ValueError("invalid shape or sampling for this library")
+        n, S = shape.n_bh, shape.seq_len
+        self.ws = torch.empty(need, dtype=torch.uint8, device=device)
+        self.col = torch.empty(n, S, dtype=torch.float32, device=device)
+        self.slash = torch.empty_like(self.col)
+        self.col_idx = torch.empty(n, S, dtype=torch.int32, device=device)
+        self.slash_idx = torch.empty_like(self.col_idx)
+        self.col_cnt = torch.empty(n, dtype=torch.int32, device=device)
+        self.slash_cnt = torch.empty_like(self.col_cnt)
+        self.tiles = torch.zeros(n, dtype=torch.int64, device=device)
+        odt = torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16
+        self.out = torch.empty(shape.batch, shape.n_q_heads, S, shape.head_dim, dtype=odt, device=device)
+
+    def _ok(self, st, where):
+        if st != 0:
+            raise SaError(st, where)
+
+    def sample(self, q, k):
+        self._ok(self.lib.sa_sample_scores(ctypes.byref(self.cs), ctypes.byref(self.sm), _ptr(q), _ptr(k),
+                                           _ptr(self.col), _ptr(self.slash), None, _ptr(self.ws),
+                                           self.ws.numel(), _stream()), "sa_sample_scores")
+
+    def select(self, alpha_c, alpha_s):
+        self._ok(self.lib.sa_select_strips(ctypes.byref(self.cs), _ptr(self.col), _ptr(self.slash),
+                                           ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
+                                           _ptr(self.col_idx), _ptr(self.col_cnt), _ptr(self.slash_idx),
+                                           _ptr(self.slash_cnt), None, 0, _stream()), "sa_select_strips")
+
+    def attend(self, q, k, v, window):
+        self._ok(self.lib.sa_sparse_attn(ctypes.byref(self.cs), _ptr(q), _ptr(k), _ptr(v), _ptr(self.col_idx),
+                                         _ptr(self.col_cnt), _ptr(self.slash_idx), _ptr(self.slash_cnt),
+                                         int(window), _ptr(self.out), self.out_dtype, None, _ptr(self.tiles),
+                                         _ptr(self.ws), self.ws.numel(), _stream()), "sa_sparse_attn")
+
+    def dense(self, q, k, v):
+        self._ok(self.lib.sa_dense_attn(ctypes.byref(self.cs), _ptr(q), _ptr(k), _ptr(v), _ptr(self.out),
+                                        self.out_dtype, None, _ptr(self.ws), self.ws.numel(), _stream()),
+                 "sa_dense_attn")
+
+    def run(self, q, k, v, alpha_c, alpha_s, window):
+        self.sample(q, k)
+        self.select(alpha_c, alpha_s)
+        self.attend(q, k, v, window)
+        return self.out
 
 
 def sample_attention(q, k, v, n_sample_rows: int, alpha_c: float, alpha_s: float, local_window: int,

@@ -89,6 +89,29 @@ size_t dense_ws(const Dims& d) { return align_up((size_t)d.n_bkv * sa::kHeadDim 
 
 inline sa_status dev(hipError_t e) { return e == hipSuccess ? SA_OK : SA_ERR_DEVICE; }
 
+// ---- optional event-pair profiling around kernels -----------------------------
+struct Profiler {
+  bool on = false;
+  bool created = false;
+  hipEvent_t start[SA_K_COUNT][SA_PROFILE_SLOTS];
+  hipEvent_t stop[SA_K_COUNT][SA_PROFILE_SLOTS];
+  long long count[SA_K_COUNT];
+} g_prof;
+
+struct Scope {   // records start now and stop at destruction
+  int k; int slot; hipStream_t st; bool live;
+  Scope(int kernel, hipStream_t s) : k(kernel), slot(0), st(s), live(g_prof.on) {
+    if (!live) return;
+    slot = (int)(g_prof.count[k] % SA_PROFILE_SLOTS);
+    (void)hipEventRecord(g_prof.start[k][slot], st);
+  }
+  ~Scope() {
+    if (!live) return;
+    (void)hipEventRecord(g_prof.stop[k][slot], st);
+    g_prof.count[k]++;
+  }
+};
+
 sa::FlashParams base_flash(const Dims& d, const void* q, const void* k) {
   sa::FlashParams P;
   memset(&P, 0, sizeof(P));
@@ -162,7 +185,10 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   P.q_row0 = d.S - n_s;
   P.n_qrows = n_s;
   P.n_qtiles = (n_s + sa::kFlashBQ - 1) / sa::kFlashBQ;
-  s = dev(sa::launch_flash(1, false, P, st));
+  {
+    Scope sc(SA_K_ROW_LSE, st);
+    s = dev(sa::launch_flash(1, false, P, st));
+  }
   if (s != SA_OK) return s;
 
   // pass 2: recompute the probabilities and accumulate columns and diagonals
@@ -175,7 +201,13 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   C.partial = reinterpret_cast<float*>(ws + w.partial);
   C.S = d.S; C.n_s = n_s; C.n_bh = d.n_bh; C.n_bkv = d.n_bkv; C.group = d.group;
   C.scale_log2 = P.scale_log2;
-  return dev(sa::launch_score_accumulate(C, st));
+  {
+    Scope sc(SA_K_SCORE_ACCUM, st);
+    s = dev(sa::launch_score_accumulate(C, st));
+  }
+  if (s != SA_OK) return s;
+  Scope sc(SA_K_SCORE_FINAL, st);
+  return dev(sa::launch_score_finalize(C, st));
 }
 
 sa_status sa_select_strips(const sa_shape* shape,
@@ -194,6 +226,7 @@ sa_status sa_select_strips(const sa_shape* shape,
   if (!(alpha_c >= 0.0f) || !(alpha_s >= 0.0f) || !isfinite(alpha_c) || !isfinite(alpha_s))
     return SA_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  Scope sc(SA_K_SELECT, st);
   sa::SelectParams P;
   P.n_prob = d.n_bh; P.S = d.S;
   P.scores = col_scores; P.idx = col_idx; P.cnt = col_cnt; P.alpha = alpha_c;
@@ -223,41 +256,44 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
 
-  // merge_index, slash side: bitmaps of kept columns / offsets and touched tile diagonals
   sa::MaskPrepParams M;
-  memset(&M, 0, sizeof(M));
-  M.col_idx = col_idx; M.col_cnt = col_cnt; M.slash_idx = slash_idx; M.slash_cnt = slash_cnt;
-  M.col_bits = reinterpret_cast<uint32_t*>(ws + w.cbits);
-  M.off_bits = reinterpret_cast<uint32_t*>(ws + w.obits);
-  M.dlist = reinterpret_cast<int32_t*>(ws + w.dlist);
-  M.dcnt = reinterpret_cast<int32_t*>(ws + w.dcnt);
-  M.n_bh = d.n_bh; M.S = d.S; M.window = local_window;
-  M.cb_words = w.cb_words; M.rb_words = w.rb_words; M.dlist_stride = w.dlist_stride; M.off_max = w.off_max;
-  s = dev(sa::launch_mask_prep(M, st));
-  if (s != SA_OK) return s;
+  {
+    Scope sc(SA_K_MASK_PREP, st);
+    // merge_index, slash side: bitmaps of kept columns / offsets and touched tile diagonals
+    memset(&M, 0, sizeof(M));
+    M.col_idx = col_idx; M.col_cnt = col_cnt; M.slash_idx = slash_idx; M.slash_cnt = slash_cnt;
+    M.col_bits = reinterpret_cast<uint32_t*>(ws + w.cbits);
+    M.off_bits = reinterpret_cast<uint32_t*>(ws + w.obits);
+    M.dlist = reinterpret_cast<int32_t*>(ws + w.dlist);
+    M.dcnt = reinterpret_cast<int32_t*>(ws + w.dcnt);
+    M.n_bh = d.n_bh; M.S = d.S; M.window = local_window;
+    M.cb_words = w.cb_words; M.rb_words = w.rb_words; M.dlist_stride = w.dlist_stride; M.off_max = w.off_max;
+    s = dev(sa::launch_mask_prep(M, st));
+    if (s != SA_OK) return s;
 
-  // V^T for the contiguous (slash / window) tiles
-  s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
-  if (s != SA_OK) return s;
+    // V^T for the contiguous (slash / window) tiles
+    s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
+    if (s != SA_OK) return s;
 
-  // merge_index, column side: compact K rows and V^T columns of the kept keys, per query head
-  sa::GatherParams G;
-  memset(&G, 0, sizeof(G));
-  G.idx = col_idx; G.cnt = col_cnt; G.idx_stride = d.S;
-  G.idx_pad = reinterpret_cast<int32_t*>(ws + w.cidx); G.idx_pad_stride = d.S_pad;
-  G.n_out = d.n_bh; G.group = d.group; G.S = d.S; G.C_pad = d.S_pad;
-  G.src = static_cast<const uint16_t*>(v);
-  G.out_t = reinterpret_cast<uint16_t*>(ws + w.vct);
-  s = dev(sa::launch_gather_transpose(G, st));
-  if (s != SA_OK) return s;
-  // K rows: gather only
-  G.src = static_cast<const uint16_t*>(k);
-  G.out_rows = reinterpret_cast<uint16_t*>(ws + w.kc);
-  G.out_t = nullptr;
-  G.idx_pad = nullptr;
-  s = dev(sa::launch_gather_transpose(G, st));
-  if (s != SA_OK) return s;
+    // merge_index, column side: compact K rows and V^T columns of the kept keys, per query head
+    sa::GatherParams G;
+    memset(&G, 0, sizeof(G));
+    G.idx = col_idx; G.cnt = col_cnt; G.idx_stride = d.S;
+    G.idx_pad = reinterpret_cast<int32_t*>(ws + w.cidx); G.idx_pad_stride = d.S_pad;
+    G.n_out = d.n_bh; G.group = d.group; G.S = d.S; G.C_pad = d.S_pad;
+    G.src = static_cast<const uint16_t*>(v);
+    G.out_t = reinterpret_cast<uint16_t*>(ws + w.vct);
+    s = dev(sa::launch_gather_transpose(G, st));
+    if (s != SA_OK) return s;
+    // K rows: gather only
+    G.src = static_cast<const uint16_t*>(k);
+    G.out_rows = reinterpret_cast<uint16_t*>(ws + w.kc);
+    G.out_t = nullptr;
+    G.idx_pad = nullptr;
+    s = dev(sa::launch_gather_transpose(G, st));
+    if (s != SA_OK) return s;
 
+  }
   if (tiles != nullptr) {
     s = dev(sa::launch_fill_u32(reinterpret_cast<uint32_t*>(tiles), 2 * (size_t)d.n_bh, 0u, st));
     if (s != SA_OK) return s;
@@ -274,6 +310,7 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
   P.tiles = reinterpret_cast<unsigned long long*>(tiles);
   P.cidx_stride = d.S_pad; P.cb_words = w.cb_words; P.rb_words = w.rb_words;
   P.dlist_stride = w.dlist_stride; P.off_max = w.off_max;
+  Scope sc(SA_K_SPARSE_FLASH, st);
   return dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
 }
 
@@ -289,11 +326,44 @@ sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, con
   if (s != SA_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint16_t* vt = static_cast<uint16_t*>(workspace);
-  s = dev(transpose_v(d, v, vt, st));
+  {
+    Scope sc(SA_K_TRANSPOSE_V, st);
+    s = dev(transpose_v(d, v, vt, st));
+  }
   if (s != SA_OK) return s;
   sa::FlashParams P = base_flash(d, q, k);
   P.vt = vt; P.out = out; P.lse = out_lse;
+  Scope sc(SA_K_DENSE_FLASH, st);
   return dev(sa::launch_flash(0, out_dtype == SA_OUT_F32, P, st));
+}
+
+sa_status sa_profile_enable(int enable) {
+  if (enable && !g_prof.created) {
+    for (int k = 0; k < SA_K_COUNT; ++k)
+      for (int i = 0; i < SA_PROFILE_SLOTS; ++i) {
+        if (hipEventCreate(&g_prof.start[k][i]) != hipSuccess) return SA_ERR_DEVICE;
+        if (hipEventCreate(&g_prof.stop[k][i]) != hipSuccess) return SA_ERR_DEVICE;
+      }
+    g_prof.created = true;
+  }
+  for (int k = 0; k < SA_K_COUNT; ++k) g_prof.count[k] = 0;
+  g_prof.on = (enable != 0);
+  return SA_OK;
+}
+
+int sa_profile_read(int kernel, float* ms, int cap) {
+  if (kernel < 0 || kernel >= SA_K_COUNT || ms == nullptr || cap < 0 || !g_prof.created) return -1;
+  long long n = g_prof.count[kernel];
+  long long first = (n > SA_PROFILE_SLOTS) ? n - SA_PROFILE_SLOTS : 0;
+  int w = 0;
+  for (long long i = first; i < n && w < cap; ++i) {
+    int slot = (int)(i % SA_PROFILE_SLOTS);
+    if (hipEventSynchronize(g_prof.stop[kernel][slot]) != hipSuccess) return -1;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_prof.start[kernel][slot], g_prof.stop[kernel][slot]) != hipSuccess) return -1;
+    ms[w++] = t;
+  }
+  return w;
 }
 
 const char* sa_status_string(int status) {

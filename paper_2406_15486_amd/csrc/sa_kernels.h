@@ -71,6 +71,7 @@ struct ScoreParams {
   int n_kblocks, n_chunks, chunk_rows, win;   // win = floats per (key block, chunk) partial
 };
 hipError_t launch_score_accumulate(const ScoreParams& P, hipStream_t st);
+hipError_t launch_score_finalize(const ScoreParams& P, hipStream_t st);
 size_t score_partial_floats(int S, int n_s, int n_bh);
 void score_geometry(int S, int n_s, int* n_kblocks, int* n_chunks, int* chunk_rows, int* win);
 

@@ -200,24 +200,34 @@ size_t score_partial_floats(int S, int n_s, int n_bh) {
   return (size_t)n_bh * nk * nc * w + (size_t)n_bh * nc * S;
 }
 
-hipError_t launch_score_accumulate(const ScoreParams& P0, hipStream_t st) {
+static ScoreParams with_geometry(const ScoreParams& P0) {
   ScoreParams P = P0;
   int cr;
   score_geometry(P.S, P.n_s, &P.n_kblocks, &P.n_chunks, &cr, &P.win);
   P.chunk_rows = cr;
-  float* colpart = P0.partial + (size_t)P.n_bh * P.n_kblocks * P.n_chunks * P.win;
-  ScoreParams A = P;
-  A.col = colpart;                 // the accumulate kernel writes per-chunk column sums
+  return P;
+}
+
+static float* column_partials(const ScoreParams& P) {
+  return P.partial + (size_t)P.n_bh * P.n_kblocks * P.n_chunks * P.win;
+}
+
+hipError_t launch_score_accumulate(const ScoreParams& P0, hipStream_t st) {
+  ScoreParams A = with_geometry(P0);
+  A.col = column_partials(A);      // the accumulate kernel writes per-chunk column sums
   size_t shmem = 4 * WWIN * 4 + 2 * QSTAGE_B;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_accumulate_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return e;
-  dim3 grid(P.n_kblocks, P.n_chunks, P.n_bh);
+  dim3 grid(A.n_kblocks, A.n_chunks, A.n_bh);
   hipLaunchKernelGGL(score_accumulate_kernel, grid, dim3(256), shmem, st, A);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_score_finalize(const ScoreParams& P0, hipStream_t st) {
+  ScoreParams P = with_geometry(P0);
   dim3 g2((P.S + 255) / 256, P.n_bh);
-  hipLaunchKernelGGL(score_finalize_kernel, g2, dim3(256), 0, st, P, colpart);
+  hipLaunchKernelGGL(score_finalize_kernel, g2, dim3(256), 0, st, P, column_partials(P));
   return hipGetLastError();
 }
 
