@@ -2,14 +2,20 @@
 // every sampled query known, recompute p_ij = exp(q_i.k_j*scale - lse_i) tile by
 // tile and accumulate it down the key columns and along the diagonals.
 //
-// One workgroup = 128 keys (4 waves x 32 keys, K resident in registers as the
-// MFMA B operand) x one chunk of sampled rows.  S = Q K^T is formed 32 rows at
+// One workgroup = 256 keys (4 waves x 64 keys, K resident in registers as two
+// MFMA B operands) x one chunk of sampled rows.  S = Q K^T is formed 32 rows at
 // a time, so one lane holds ONE key (lane % 32) and 16 query rows: the column
-// sum is in-lane arithmetic.  Diagonal sums go to a per-wave LDS window with
-// LDS float adds (each wave adds in its own program order), the four windows are
-// combined in a fixed order and written as one partial per (key block, chunk);
-// a second kernel adds the partials in a fixed order.  No global float atomics:
-// repeated runs give identical bits.
+// sum is in-lane arithmetic.  For the diagonals, the tile (row block b, key
+// sub-block kb) has exactly the lane/register -> diagonal mapping of every other
+// tile with the same b - kb, so tiles of one diagonal class are first added up
+// in registers; a finished class is added into a window in LDS that is private
+// to the wave and to the lane half (plain read-add-write: no two lanes of one
+// instruction share a slot, and a wave's LDS operations execute in order).
+// The eight windows are combined in a fixed order into one partial per (key
+// block, chunk) and a second kernel adds the partials in a fixed order.  No
+// float atomics anywhere: repeated runs give identical bits.
+#include <type_traits>
+
 #include "sa_device.h"
 #include "sa_kernels.h"
 
@@ -17,17 +23,19 @@ namespace sa {
 
 namespace {
 
-constexpr int KB = 128;          // keys per workgroup
-constexpr int QC = 2048;         // sampled rows per chunk
-constexpr int WWIN = QC + 64;    // floats in one wave's diagonal window
-constexpr int WIN = QC + 128;    // floats in the combined (key block, chunk) partial
+typedef __attribute__((address_space(3))) float lds_f32;   // LDS-qualified, keeps ds_ instructions
+
+constexpr int KB = 256;          // keys per workgroup (4 waves x 2 sub-blocks x 32)
+constexpr int QC = 1024;         // sampled rows per chunk
+constexpr int WWIN = QC + 64;    // floats in one (wave, lane half) diagonal window
+constexpr int WIN = QC + 256;    // floats in the combined (key block, chunk) partial
 constexpr int QROW_B = 272;      // bytes per staged Q row
 constexpr int QSTAGE_B = 32 * QROW_B + 32 * 4;   // 32 rows + 32 lse values
 
-__global__ __launch_bounds__(256) void score_accumulate_kernel(ScoreParams P) {
+__global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  float* win = reinterpret_cast<float*>(smem);                  // [4][WWIN]
-  char* qstage = smem + 4 * WWIN * 4;                           // [2][QSTAGE_B]
+  float* win = reinterpret_cast<float*>(smem);                  // [4 waves][2 halves][WWIN]
+  char* qstage = smem + 8 * WWIN * 4;                           // [2][QSTAGE_B]
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int ql = lane & 31, hf = lane >> 5;
@@ -38,54 +46,49 @@ __global__ __launch_bounds__(256) void score_accumulate_kernel(ScoreParams P) {
   const int row_end = min(row0 + QC, S);            // one past the last row
   const int j0 = kb * KB;
   if (row_end - 1 < j0) return;                     // chunk entirely above these keys
-  const int jw = j0 + 32 * wave;
-  const int j_me = jw + ql;
+  const int jw = j0 + 64 * wave;
   const int bkv = bh / P.group;
   const float c2 = P.scale_log2;
 
-  // K^T operand of this wave's 32 keys (zero beyond the sequence end)
-  bf16x8 kf[8];
-  {
-    const uint16_t* krow = P.k + ((size_t)bkv * S + min(j_me, S - 1)) * kHeadDim;
+  // K^T operands of this wave's 2 x 32 keys (zero beyond the sequence end)
+  bf16x8 kf[2][8];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    int j = jw + 32 * sb + ql;
+    const uint16_t* krow = P.k + ((size_t)bkv * S + min(j, S - 1)) * kHeadDim;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       uint4 v = *reinterpret_cast<const uint4*>(krow + ks * 16 + hf * 8);
-      if (j_me >= S) v = make_uint4(0u, 0u, 0u, 0u);
-      kf[ks] = as_bf16x8(v);
+      if (j >= S) v = make_uint4(0u, 0u, 0u, 0u);
+      kf[sb][ks] = as_bf16x8(v);
     }
   }
-  for (int x = tid; x < 4 * WWIN; x += 256) win[x] = 0.f;
+  for (int x = tid; x < 8 * WWIN; x += 256) win[x] = 0.f;
 
-  // first 32-row block that reaches the keys of the workgroup
+  // first 32-row block that reaches the keys of the workgroup, rounded down to even
   const int nblk = (row_end - row0 + 31) / 32;
-  int b_first = (j0 > row0) ? (j0 - row0) / 32 : 0;
+  const int b_first = ((j0 > row0) ? (j0 - row0) / 32 : 0) & ~1;
   const uint16_t* qbase = P.q + (size_t)bh * S * kHeadDim;
   const float* lbase = P.lse + (size_t)bh * P.n_s;
 
-  uint4 pq[2];
+  uint4 pq0, pq1;
   float pl = 0.f;
+  const int qrow_t = tid >> 4, qcol_t = tid & 15;
   auto load_block = [&](int b) {
     int rb = row0 + 32 * b;
-#pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      int c = tid + 256 * n;
-      int row = c >> 4, col = c & 15;
-      int i = rb + row;
-      pq[n] = (i < S) ? *reinterpret_cast<const uint4*>(qbase + (size_t)i * kHeadDim + col * 8)
-                      : make_uint4(0u, 0u, 0u, 0u);
-    }
+    int i0 = rb + qrow_t, i1 = i0 + 16;
+    pq0 = make_uint4(0u, 0u, 0u, 0u);
+    pq1 = make_uint4(0u, 0u, 0u, 0u);
+    if (i0 < S) pq0 = *reinterpret_cast<const uint4*>(qbase + (size_t)i0 * kHeadDim + qcol_t * 8);
+    if (i1 < S) pq1 = *reinterpret_cast<const uint4*>(qbase + (size_t)i1 * kHeadDim + qcol_t * 8);
     if (tid < 32) {
       int i = rb + tid;
       pl = (i < S) ? lbase[i - r0] * kLog2e : 0.f;
     }
   };
   auto store_block = [&](char* st) {
-#pragma unroll
-    for (int n = 0; n < 2; ++n) {
-      int c = tid + 256 * n;
-      int row = c >> 4, col = c & 15;
-      *reinterpret_cast<uint4*>(st + row * QROW_B + col * 16) = pq[n];
-    }
+    *reinterpret_cast<uint4*>(st + qrow_t * QROW_B + qcol_t * 16) = pq0;
+    *reinterpret_cast<uint4*>(st + (qrow_t + 16) * QROW_B + qcol_t * 16) = pq1;
     if (tid < 32) reinterpret_cast<float*>(st + 32 * QROW_B)[tid] = pl;
   };
 
@@ -95,60 +98,118 @@ __global__ __launch_bounds__(256) void score_accumulate_kernel(ScoreParams P) {
   }
   __syncthreads();
 
-  float colacc = 0.f;
-  float* mywin = win + wave * WWIN;
-  for (int b = b_first; b < nblk; ++b) {
-    const char* st = qstage + (b & 1) * QSTAGE_B;
-    const bool have_next = (b + 1 < nblk);
-    if (have_next) load_block(b + 1);
-    const int rb = row0 + 32 * b;
-    if (rb + 31 >= jw) {          // some row of the block reaches this wave's keys
-      f32x16 s;
+  float colacc[2] = {0.f, 0.f};
+  f32x16 dacc[2];                 // diagonal classes (b - sb) even / odd
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+  for (int r = 0; r < 16; ++r) { dacc[0][r] = 0.f; dacc[1][r] = 0.f; }
+  // slot of (row rb + m, key jw + 32 sb + ql) in this wave's window:
+  //   32 (b - sb + 1) + (m - ql) + 31
+  float* mywin = win + (wave * 2 + hf) * WWIN + 31 - ql + 4 * hf;
+
+  // one 32-row block against both key sub-blocks; PAR = parity of b (compile time)
+  auto do_block = [&](int b, auto par_tag) {
+    constexpr int PAR = decltype(par_tag)::value;
+    const char* st = qstage + (b & 1) * QSTAGE_B;
+    const int rb = row0 + 32 * b;
+    if (rb + 31 >= jw) {            // some row reaches this wave's first sub-block
+      bf16x8 qf[8];
       const char* qp = st + ql * QROW_B + hf * 16;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        bf16x8 qf = as_bf16x8(*reinterpret_cast<const uint4*>(qp + ks * 32));
-        s = mfma_32x32x16(qf, kf[ks], s);
-      }
-      // element r: query row rb + 8*(r/4) + 4*hf + r%4, key j_me
+      for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(qp + ks * 32));
       const float* ls = reinterpret_cast<const float*>(st + 32 * QROW_B);
-      const bool edge = (rb < jw + 32) || (rb + 32 > S);
-      const int wbase = (rb - row0) - ql + 31;    // window slot of (row rb, key j_me)
+      float lv[16];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         float4 l4 = *reinterpret_cast<const float4*>(ls + 8 * g + 4 * hf);
-        float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+        lv[4 * g] = l4.x; lv[4 * g + 1] = l4.y; lv[4 * g + 2] = l4.z; lv[4 * g + 3] = l4.w;
+      }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          int m = 8 * g + 4 * hf + t;
-          float p = fast_exp2(fmaf(s[4 * g + t], c2, -lv[t]));
-          if (edge) {
-            int i = rb + m;
-            p = (i >= j_me && i < S) ? p : 0.f;
+      for (int sb = 0; sb < 2; ++sb) {
+        const int jsb = jw + 32 * sb;
+        if (rb + 31 >= jsb) {
+          f32x16 s;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) s = mfma_32x32x16(qf[ks], kf[sb][ks], s);
+          // element r: query row rb + 8*(r/4) + 4*hf + r%4, key jsb + ql
+          const bool edge = (rb < jsb + 32) || (rb + 32 > S);
+          const int j_me = jsb + ql;
+          float csum = 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float p = fast_exp2(fmaf(s[r], c2, -lv[r]));
+            if (edge) {
+              int i = rb + 8 * (r >> 2) + 4 * hf + (r & 3);
+              p = (i >= j_me && i < S) ? p : 0.f;
+            }
+            csum += p;
+            dacc[(PAR + sb) & 1][r] += p;
           }
-          colacc += p;
-          atomicAdd(mywin + wbase + m, p);
+          colacc[sb] += csum;
         }
       }
     }
-    if (have_next) store_block(qstage + ((b + 1) & 1) * QSTAGE_B);
+    // class b - 1 (tiles (b-1, 0) and (b, 1)) is complete: add it into the window
+    {
+      constexpr int C = (PAR + 1) & 1;
+      float* wp = mywin + 32 * b;              // 32 * ((b - 1) + 1)
+      // One register at a time: two registers of different lanes can name the
+      // same slot, so every read-add-write must finish (LDS executes a wave's
+      // operations in order) before the next register's starts.
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        volatile lds_f32* slot = (volatile lds_f32*)(wp + 8 * (r >> 2) + (r & 3));
+        *slot = *slot + dacc[C][r];
+        dacc[C][r] = 0.f;
+      }
+    }
+  };
+
+  for (int b = b_first; b < nblk; b += 2) {
+    // even block
+    if (b + 1 < nblk) load_block(b + 1);
+    do_block(b, std::integral_constant<int, 0>{});
+    if (b + 1 < nblk) store_block(qstage + ((b + 1) & 1) * QSTAGE_B);
+    __syncthreads();
+    if (b + 1 >= nblk) break;
+    // odd block
+    if (b + 2 < nblk) load_block(b + 2);
+    do_block(b + 1, std::integral_constant<int, 1>{});
+    if (b + 2 < nblk) store_block(qstage + ((b + 2) & 1) * QSTAGE_B);
     __syncthreads();
   }
+  // the last class (only its sub-block-0 tile exists): b = nblk - 1
+  {
+    const int bl = nblk;                      // class nblk - 1 -> slot base 32 * nblk
+    float* wp = mywin + 32 * bl;
+    const int C = (nblk - 1) & 1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float add = (C == 0) ? dacc[0][r] : dacc[1][r];
+      volatile lds_f32* slot = (volatile lds_f32*)(wp + 8 * (r >> 2) + (r & 3));
+      *slot = *slot + add;
+    }
+  }
+  __syncthreads();
 
   // column sums of this chunk (both lane halves hold disjoint rows)
-  float ctot = colacc + swap_half(colacc);
-  if (hf == 0 && j_me < S) P.col[((size_t)bh * P.n_chunks + ch) * S + j_me] = ctot;
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    float ctot = colacc[sb] + swap_half(colacc[sb]);
+    int j = jw + 32 * sb + ql;
+    if (hf == 0 && j < S) P.col[((size_t)bh * P.n_chunks + ch) * S + j] = ctot;
+  }
 
-  // combine the four wave windows: slot x <-> offset x + (row0 - j0 - 127)
+  // combine the eight windows: slot x <-> offset x + (row0 - j0 - 255);
+  // wave w slot y <-> offset y + (row0 - j0 - 64 w - 63)
   float* out = P.partial + (((size_t)bh * P.n_kblocks + kb) * P.n_chunks + ch) * WIN;
   for (int x = tid; x < WIN; x += 256) {
     float acc = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      int y = x - 96 + 32 * w;
-      if (y >= 0 && y < WWIN) acc += win[w * WWIN + y];
+      int y = x - 192 + 64 * w;
+      if (y >= 0 && y < WWIN) acc += win[(w * 2) * WWIN + y] + win[(w * 2 + 1) * WWIN + y];
     }
     out[x] = acc;
   }
@@ -168,15 +229,15 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(ScoreParams P, cons
     int row_end = min(row0 + QC, S);
     // column x
     if (row_end - 1 >= (x / KB) * KB) c += (double)colpart[((size_t)bh * P.n_chunks + ch) * S + x];
-    // offset x: slot = x - row0 + 128 kb + 127 in [0, WIN)
-    int kb_lo = row0 - x - 127;                       // 128 kb >= kb_lo
+    // offset x: slot = x - row0 + KB kb + (KB - 1) in [0, WIN)
+    int kb_lo = row0 - x - (KB - 1);                  // KB kb >= kb_lo
     kb_lo = (kb_lo <= 0) ? 0 : (kb_lo + KB - 1) / KB;
-    int kb_hi_num = row0 - x + WIN - 1 - 127;         // 128 kb <= kb_hi_num
+    int kb_hi_num = row0 - x + WIN - 1 - (KB - 1);    // KB kb <= kb_hi_num
     if (kb_hi_num < 0) continue;
     int kb_hi = min(kb_hi_num / KB, P.n_kblocks - 1);
     for (int kb = kb_lo; kb <= kb_hi; ++kb) {
       if (row_end - 1 < kb * KB) break;               // block not live for this chunk
-      int slot = x - row0 + KB * kb + 127;
+      int slot = x - row0 + KB * kb + (KB - 1);
       s += (double)P.partial[(((size_t)bh * P.n_kblocks + kb) * P.n_chunks + ch) * WIN + slot];
     }
   }
@@ -215,7 +276,7 @@ static float* column_partials(const ScoreParams& P) {
 hipError_t launch_score_accumulate(const ScoreParams& P0, hipStream_t st) {
   ScoreParams A = with_geometry(P0);
   A.col = column_partials(A);      // the accumulate kernel writes per-chunk column sums
-  size_t shmem = 4 * WWIN * 4 + 2 * QSTAGE_B;
+  size_t shmem = 8 * WWIN * 4 + 2 * QSTAGE_B;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_accumulate_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return e;
