@@ -28,6 +28,7 @@ constexpr int KTILE_B = BK * KROW_B;
 constexpr int VTILE_B = kHeadDim * VROW_B;
 constexpr int IDX_B = BK * 4;
 constexpr int STAGE_B = KTILE_B + VTILE_B + IDX_B;
+constexpr float kLazy = 8.0f;         // rescale only when a row maximum grows by more than 2^8
 
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
 
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
   constexpr bool WITH_V = (MODE != 1);
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
   const int lane = tid & 63;
   const int ql = lane & 31;   // query within the wave / row within a 32-row operand
   const int hf = lane >> 5;   // which half of the contraction block this lane feeds
@@ -234,12 +235,13 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
       tile_load(Tn);
     }
 
-    bool skip = false;
+    // nothing to do for this wave when every key of the tile lies after all its rows
+    bool skip = (T.kind != TK_COLIDX) && (T.j0 > iw0 + 31);
     if (MODE == 2 && T.kind == TK_RANGE) {
       // every key of the tile already belongs to a selected column: the
       // column pass has covered it, nothing is left for the range pass
       uint32_t w0 = cbits[T.j0 >> 5], w1 = cbits[(T.j0 >> 5) + 1];
-      skip = ((w0 & w1) == 0xFFFFFFFFu) || (T.rows <= 0);   // or the tile lies past the sequence end
+      skip = skip || ((w0 & w1) == 0xFFFFFFFFu) || (T.rows <= 0);   // or the tile lies past the sequence end
     }
 
     if (!skip) {
@@ -312,9 +314,22 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
       mx = fmaxf(mx, swap_half(mx));
-      float m_new = fmaxf(m_run, mx * c2);
-      float alpha = fast_exp2(m_run - m_new);
-      m_run = m_new;
+      // lazy rescale: keep the old reference maximum unless it grew by more than
+      // 2^kLazy (probabilities then stay <= 2^kLazy, exact in fp32 and bf16 alike)
+      const float m_cand = mx * c2;
+      const bool grow = m_cand > m_run + kLazy;
+      if (__any(grow)) {
+        float m_new = grow ? m_cand : m_run;
+        float alpha = fast_exp2(m_run - m_new);
+        m_run = m_new;
+        l_run *= alpha;
+        if (WITH_V) {
+#pragma unroll
+          for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
+        }
+      }
       float rs = 0.f;
       uint32_t pk[2][8];
 #pragma unroll
@@ -322,21 +337,15 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_new));
+          p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_run));
           rs += p[r];
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) pk[sb][r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
       }
-      l_run = fmaf(l_run, alpha, rs);
+      l_run += rs;
 
       if (WITH_V) {
-        if (__any(alpha != 1.0f)) {
-#pragma unroll
-          for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
-        }
         // ---- O^T += V^T P^T ---------------------------------------------------
         const char* vp = stage + KTILE_B + ql * VROW_B + hf * 16;
 #pragma unroll
@@ -361,7 +370,7 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
 
   // ---- epilogue -------------------------------------------------------------
   float l_tot = l_run + swap_half(l_run);
-  if (MODE == 2 && P.tiles != nullptr && tid == 0) atomicAdd(P.tiles + bh, tiles_done);
+  if (MODE == 2 && P.tiles != nullptr && lane == 0) atomicAdd(P.tiles + bh, tiles_done);
   if (!row_ok) return;
   if (P.lse != nullptr && hf == 0) {
     size_t at = (MODE == 1) ? ((size_t)bh * P.n_qrows + (i_me - P.q_row0)) : ((size_t)bh * S + i_me);

@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
   float* win = reinterpret_cast<float*>(smem);                  // [4 waves][2 halves][WWIN]
   char* qstage = smem + 8 * WWIN * 4;                           // [2][QSTAGE_B]
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int ql = lane & 31, hf = lane >> 5;
   const int kb = blockIdx.x, ch = blockIdx.y, bh = blockIdx.z;
   const int S = P.S;
