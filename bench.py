@@ -59,8 +59,10 @@ def mask_density(S: int, cols: np.ndarray, offs: np.ndarray, window: int) -> flo
     return (n_col + n_off - both) / (S * (S + 1) / 2.0)
 
 
-def cpu_baseline(wl, x, alpha: float, budget_rows: int, attend_rows: int) -> dict:
-    """Oracle timing on a bounded sample, scaled to ms per layer."""
+def cpu_baseline(wl, x, alpha: float, budget_s: float) -> dict:
+    """Oracle timing on a bounded sample (about 2 x budget_s of CPU work), scaled
+    linearly to ms per layer.  The oracle runs as it stands: numpy fp64 on the
+    host cores of this machine."""
     from oracle import sample_attention as O        # CPU-baseline leg only
     from sa_inputs import bf16_bits_to_f32
     try:
@@ -72,23 +74,32 @@ def cpu_baseline(wl, x, alpha: float, budget_rows: int, attend_rows: int) -> dic
     q = bf16_bits_to_f32(x["q"][0]).astype(np.float64)
     k = bf16_bits_to_f32(x["k"][0]).astype(np.float64)
     v = bf16_bits_to_f32(x["v"][0]).astype(np.float64)
-    rows1 = min(budget_rows, n_s)
-    t0 = time.perf_counter()
-    col, slash, _ = O.sample_scores(q, k, rows1)
-    t1 = time.perf_counter()
+
+    def timed(fn):
+        t0 = time.perf_counter()
+        r = fn()
+        return r, time.perf_counter() - t0
+
+    # stage 1: probe with a few rows, then size the sample to the budget
+    probe = min(64, n_s)
+    _, tp = timed(lambda: O.sample_scores(q, k, probe))
+    rows1 = int(min(n_s, max(probe, 64 * int(budget_s / max(tp, 1e-6) * probe / 64))))
+    (col, slash, _), t1 = timed(lambda: O.sample_scores(q, k, rows1))
     a32 = float(np.float32(alpha))
-    Ic, Is = O.select(col, a32), O.select(slash, a32)
-    t2 = time.perf_counter()
-    rows = np.linspace(0, S - 1, attend_rows).astype(np.int64)
-    O.masked_attn(q, k, v, Ic, Is, wl.window, rows=rows)
-    t3 = time.perf_counter()
-    per_head = (t1 - t0) * (n_s / rows1) + (t2 - t1) + (t3 - t2) * (S / attend_rows)
+    (Ic, Is), t2 = timed(lambda: (O.select(col, a32), O.select(slash, a32)))
+    # attention: same idea
+    pr = np.linspace(0, S - 1, 8).astype(np.int64)
+    _, tp = timed(lambda: O.masked_attn(q, k, v, Ic, Is, wl.window, rows=pr))
+    n_att = int(min(S, max(8, budget_s / max(tp, 1e-6) * 8)))
+    rows = np.linspace(0, S - 1, n_att).astype(np.int64)
+    _, t3 = timed(lambda: O.masked_attn(q, k, v, Ic, Is, wl.window, rows=rows))
+    per_head = t1 * (n_s / rows1) + t2 + t3 * (S / n_att)
     layer_ms = per_head * wl.n_q_heads * 1e3
     return {
         "value": layer_ms, "unit": "ms/layer", "cores": int(cores), "kind": "oracle",
         "sample": (f"query head 0 of {wl.n_q_heads}: stage 1 on the last {rows1} of {n_s} sampled rows "
-                   f"({t1 - t0:.2f} s), selection on those scores ({t2 - t1:.2f} s), masked attention on "
-                   f"{attend_rows} of {S} rows ({t3 - t2:.2f} s); scaled linearly to all rows and heads"),
+                   f"({t1:.2f} s), selection on those scores ({t2:.2f} s), masked attention on "
+                   f"{n_att} of {S} rows ({t3:.2f} s); scaled linearly to all rows and heads"),
     }
 
 
@@ -105,8 +116,10 @@ def main() -> int:
     ap.add_argument("--dense-iters", type=int, default=2)
     ap.add_argument("--no-sweep", action="store_true", help="skip the alpha sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=768)
-    ap.add_argument("--cpu-attend-rows", type=int, default=48)
+    ap.add_argument("--copy-calib-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (calibrates HBM byte counters)")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0,
+                    help="CPU work per oracle leg (stage 1, attention) of the cpu_baseline sample")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); run with --gpus 1", file=sys.stderr)
@@ -135,6 +148,15 @@ def main() -> int:
     shape = sa.Shape(1, Hq, Hkv, S)
     plan = sa.SampleAttentionPlan(shape, n_s)
     torch.cuda.synchronize()
+
+    if args.copy_calib_mib > 0:
+        # a plain copy of known size: what FETCH_SIZE / WRITE_SIZE read for it scales the counters
+        src = torch.empty(args.copy_calib_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: K whole steps ----------------------------------------------
     for _ in range(args.warmup):
@@ -214,8 +236,16 @@ def main() -> int:
     cpu = None
     if not args.no_cpu_baseline:
         t0 = time.perf_counter()
-        cpu = cpu_baseline(wl, x, args.alpha, args.cpu_rows, args.cpu_attend_rows)
+        cpu = cpu_baseline(wl, x, args.alpha, args.cpu_seconds)
         log(f"cpu baseline took {time.perf_counter() - t0:.1f} s: {cpu['value']:.0f} ms/layer")
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{wl.name}_alpha{args.alpha:g}.json")
+    if os.path.exists(tpath):
+        # HBM bytes per launch of the strip-masked flash kernel, from the committed rocprofv3 --pmc
+        # FETCH_SIZE / WRITE_SIZE runs of this same command (see the file for the calibration)
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
 
     line = {
         "metric": "sparse prefill attention ms/layer",
@@ -239,7 +269,7 @@ def main() -> int:
         "roofline": {
             "kernel": "flash_kernel<strip-masked>", "bound": "mfma", "achieved": achieved,
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": None,
+            "traffic": traffic,
             "flop_per_launch": flop, "kernel_ms": flash_ms,
         },
         "cpu_baseline": cpu,
