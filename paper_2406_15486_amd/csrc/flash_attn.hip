@@ -22,8 +22,10 @@ namespace {
 constexpr int BQ = kFlashBQ;          // 128 query rows per workgroup
 constexpr int BK = kFlashBK;          // 64 keys per tile
 constexpr int NT = 256;
-constexpr int KROW_B = 272;           // bytes per K row in LDS (256 + 16 pad: conflict-free b128 reads)
-constexpr int VROW_B = 144;           // bytes per V^T row in LDS (128 + 16 pad)
+// LDS tiles are unpadded (the direct global->LDS loads write 1 KB runs); bank
+// conflicts are avoided by XOR-swizzling the 16-byte chunk index with the row.
+constexpr int KROW_B = 256;           // bytes per K row in LDS: 16 chunks, chunk c of row p stored at c ^ (p & 15)
+constexpr int VROW_B = 128;           // bytes per V^T row in LDS: 8 chunks, chunk c of row d stored at c ^ ((d >> 1) & 7)
 constexpr int KTILE_B = BK * KROW_B;
 constexpr int VTILE_B = kHeadDim * VROW_B;
 constexpr int IDX_B = BK * 4;
@@ -33,14 +35,18 @@ constexpr float kLazy = 8.0f;         // rescale only when a row maximum grows b
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
 
 struct Tile {
-  const uint16_t* k;    // first K row of the tile (row stride 128 elements)
+  const uint16_t* kb;   // K array the tile's rows come from (row stride 128 elements)
   const uint16_t* vt;   // &V^T[0][first key] (row stride vt_stride elements)
   const int32_t* idx;   // key index of each of the 64 rows (TK_COLIDX) or null
+  int krow0;            // first row of the tile in kb
+  int kmax;             // last row of kb that may be read (rows past it are clamped: they are masked anyway)
   int vt_stride;
-  int rows;             // valid K rows (rest read as zero)
+  int rows;             // rows of the tile that are real keys
   int j0;               // first key index (contiguous tiles)
   int kind;
 };
+
+typedef __attribute__((address_space(3))) void lds_void;
 
 }  // namespace
 
@@ -153,7 +159,9 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
   auto get_tile = [&](int t) -> Tile {
     Tile T;
     if (MODE == 2 && t < n_col_tiles) {
-      T.k = kc + (size_t)t * BK * kHeadDim;
+      T.kb = kc;
+      T.krow0 = t * BK;
+      T.kmax = P.S_pad - 1;
       T.vt = vct + t * BK;
       T.vt_stride = P.S_pad;
       T.idx = cidx + t * BK;
@@ -171,7 +179,9 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
         j0 = t * BK;
         T.kind = (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
       }
-      T.k = kbase + (size_t)j0 * kHeadDim;
+      T.kb = kbase;
+      T.krow0 = j0;
+      T.kmax = S - 1;
       T.vt = WITH_V ? vtbase + j0 : nullptr;
       T.vt_stride = P.S_pad;
       T.idx = nullptr;
@@ -181,59 +191,53 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
     return T;
   };
 
-  // global -> registers -> LDS staging of one tile (K rows, V^T rows, key indices).
-  // Thread t moves 16-byte chunks t, t+256, t+512, t+768 of the K tile (16 chunks per
-  // row) and of the V^T tile (8 chunks per row).  Named registers, not arrays, so
-  // the prefetch never lands in scratch memory.
-  uint4 pk0, pk1, pk2, pk3, pv0, pv1, pv2, pv3;
-  pk0 = pk1 = pk2 = pk3 = pv0 = pv1 = pv2 = pv3 = make_uint4(0u, 0u, 0u, 0u);
-  int32_t pfi = 0;
-  const int krow_t = tid >> 4, kcol_t = tid & 15;     // + 16 rows per step
-  const int vrow_t = tid >> 3, vcol_t = tid & 7;      // + 32 rows per step
-  auto ld_k = [&](const Tile& t, int n) -> uint4 {
-    int row = krow_t + 16 * n;
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (row < t.rows) v = *reinterpret_cast<const uint4*>(t.k + (size_t)row * kHeadDim + kcol_t * 8);
-    return v;
+  // Staging of one tile with direct global -> LDS loads (no registers in between).
+  // One wave instruction writes a 1 KB run of LDS, lane l its bytes [16 l, 16 l + 16):
+  // for K that is 4 physical rows, for V^T 8 rows.  Each lane therefore fetches the
+  // global chunk that belongs at its LDS position: the K row whose slot it is (bits 2
+  // and 3 of the row index exchanged, see krow_slot) and the chunk that the XOR
+  // swizzle maps there.  Wave w issues runs w, w+4, w+8, w+12 of either tile.
+  int koff[4], voff[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    int run = wave + 4 * n;
+    int p = 4 * run + (lane >> 4);                 // physical K row
+    int c = (lane & 15) ^ (p & 15);                // logical 16-byte chunk stored there
+    koff[n] = (krow_slot(p) << 16) | (c * 8);      // key row within the tile, element offset in the row
+    int d = 8 * run + (lane >> 3);                 // V^T row
+    int cv = (lane & 7) ^ ((d >> 1) & 7);
+    voff[n] = (d << 16) | (cv * 8);
+  }
+  auto tile_dma = [&](const Tile& T, char* stage) {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      int run = wave + 4 * n;
+      int row = min(T.krow0 + (koff[n] >> 16), T.kmax);
+      const uint16_t* g = T.kb + (size_t)row * kHeadDim + (koff[n] & 0xFFFF);
+      __builtin_amdgcn_global_load_lds(g, (lds_void*)(stage + 1024 * run), 16, 0, 0);
+    }
+    if (WITH_V) {
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        int run = wave + 4 * n;
+        const uint16_t* g = T.vt + (size_t)(voff[n] >> 16) * T.vt_stride + (voff[n] & 0xFFFF);
+        __builtin_amdgcn_global_load_lds(g, (lds_void*)(stage + KTILE_B + 1024 * run), 16, 0, 0);
+      }
+    }
+    if (MODE == 2 && T.idx != nullptr && wave == 0)
+      __builtin_amdgcn_global_load_lds(T.idx + lane, (lds_void*)(stage + KTILE_B + VTILE_B), 4, 0, 0);
   };
-  auto ld_v = [&](const Tile& t, int n) -> uint4 {
-    int drow = vrow_t + 32 * n;
-    return *reinterpret_cast<const uint4*>(t.vt + (size_t)drow * t.vt_stride + vcol_t * 8);
-  };
-  auto tile_load = [&](const Tile& t) {
-    pk0 = ld_k(t, 0); pk1 = ld_k(t, 1); pk2 = ld_k(t, 2); pk3 = ld_k(t, 3);
-    if (WITH_V) { pv0 = ld_v(t, 0); pv1 = ld_v(t, 1); pv2 = ld_v(t, 2); pv3 = ld_v(t, 3); }
-    if (MODE == 2) pfi = (t.idx != nullptr && tid < BK) ? t.idx[tid] : 0;
-  };
-  auto st_k = [&](char* stage, int n, uint4 v) {
-    *reinterpret_cast<uint4*>(stage + krow_slot(krow_t + 16 * n) * KROW_B + kcol_t * 16) = v;
-  };
-  auto st_v = [&](char* stage, int n, uint4 v) {
-    *reinterpret_cast<uint4*>(stage + KTILE_B + (vrow_t + 32 * n) * VROW_B + vcol_t * 16) = v;
-  };
-  auto tile_store = [&](char* stage, bool with_idx) {
-    st_k(stage, 0, pk0); st_k(stage, 1, pk1); st_k(stage, 2, pk2); st_k(stage, 3, pk3);
-    if (WITH_V) { st_v(stage, 0, pv0); st_v(stage, 1, pv1); st_v(stage, 2, pv2); st_v(stage, 3, pv3); }
-    if (MODE == 2 && with_idx && tid < BK) reinterpret_cast<int32_t*>(stage + KTILE_B + VTILE_B)[tid] = pfi;
-  };
+  auto tile_wait = [&]() { __builtin_amdgcn_s_waitcnt(0x0f70); };   // vmcnt(0): this wave's direct loads have landed
 
   unsigned long long tiles_done = 0;
-  if (n_tiles > 0) {
-    Tile T0 = get_tile(0);
-    tile_load(T0);
-    tile_store(smem, T0.kind == TK_COLIDX);
-  }
+  if (n_tiles > 0) tile_dma(get_tile(0), smem);
+  tile_wait();
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
     char* stage = smem + (t & 1) * STAGE_B;
     Tile T = get_tile(t);
-    Tile Tn;
-    const bool have_next = (t + 1 < n_tiles);
-    if (have_next) {
-      Tn = get_tile(t + 1);
-      tile_load(Tn);
-    }
+    if (t + 1 < n_tiles) tile_dma(get_tile(t + 1), smem + ((t + 1) & 1) * STAGE_B);
 
     // nothing to do for this wave when every key of the tile lies after all its rows
     bool skip = (T.kind != TK_COLIDX) && (T.j0 > iw0 + 31);
@@ -252,10 +256,12 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
       for (int sb = 0; sb < 2; ++sb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
-        const char* kp = stage + (32 * sb + ql) * KROW_B + hf * 16;
+        // row p = 32 sb + ql; logical chunk 2 ks + hf lives at physical chunk (2 ks + hf) ^ (p & 15)
+        const char* kp = stage + (32 * sb + ql) * KROW_B;
+        const int ksw = ql & 15;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          bf16x8 kf = as_bf16x8(*reinterpret_cast<const uint4*>(kp + ks * 32));
+          bf16x8 kf = as_bf16x8(*reinterpret_cast<const uint4*>(kp + (((2 * ks + hf) ^ ksw) << 4)));
           s[sb] = mfma_32x32x16(kf, qf[ks], s[sb]);
         }
       }
@@ -347,7 +353,9 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
 
       if (WITH_V) {
         // ---- O^T += V^T P^T ---------------------------------------------------
-        const char* vp = stage + KTILE_B + ql * VROW_B + hf * 16;
+        // row d = 32 mb + ql; logical chunk 4 sb + 2 u + hf lives at physical chunk (..) ^ ((d >> 1) & 7)
+        const char* vp = stage + KTILE_B + ql * VROW_B;
+        const int vsw = (ql >> 1) & 7;
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -356,15 +364,14 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
             bf16x8 pb = as_bf16x8(pw);
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
-              bf16x8 vf = as_bf16x8(*reinterpret_cast<const uint4*>(vp + mb * 32 * VROW_B + (32 * sb + 16 * u) * 2));
+              bf16x8 vf = as_bf16x8(*reinterpret_cast<const uint4*>(vp + mb * 32 * VROW_B + (((4 * sb + 2 * u + hf) ^ vsw) << 4)));
               o[mb] = mfma_32x32x16(vf, pb, o[mb]);
             }
           }
       }
     }
 
-    if (have_next)
-      tile_store(smem + ((t + 1) & 1) * STAGE_B, Tn.kind == TK_COLIDX);
+    tile_wait();
     __syncthreads();
   }
 
