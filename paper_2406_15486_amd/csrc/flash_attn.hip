@@ -67,15 +67,15 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
   {
     const int bid = blockIdx.x;
     if (MODE == 2) {
-      // heads are sliced over the 8 XCDs (workgroups go round-robin to XCDs)
-      // so that the query tiles of one head, which stream the same gathered
-      // columns, run on the same L2; heavy (late) query tiles first.
+      // heads are sliced over the 8 XCDs (workgroups go round-robin to XCDs) and an
+      // XCD works through one head at a time, heavy (late) query tiles first: the
+      // workgroups resident on it then stream the gathered columns of the same head,
+      // a working set (tens of MB per XCD) that the memory-side cache can hold.
       if (P.n_bh >= 8) {
         int xcd = bid & 7, slot = bid >> 3;
-        int per = (P.n_bh + 7) >> 3;
-        a = P.n_qtiles - 1 - slot / per;
-        bh = xcd + 8 * (slot % per);
-        if (bh >= P.n_bh || a < 0) return;
+        a = P.n_qtiles - 1 - slot % P.n_qtiles;
+        bh = xcd + 8 * (slot / P.n_qtiles);
+        if (bh >= P.n_bh) return;
       } else {
         a = P.n_qtiles - 1 - bid / P.n_bh;
         bh = bid % P.n_bh;
@@ -224,8 +224,19 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
         __builtin_amdgcn_global_load_lds(g, (lds_void*)(stage + KTILE_B + 1024 * run), 16, 0, 0);
       }
     }
-    if (MODE == 2 && T.idx != nullptr && wave == 0)
-      __builtin_amdgcn_global_load_lds(T.idx + lane, (lds_void*)(stage + KTILE_B + VTILE_B), 4, 0, 0);
+    if (MODE == 2 && wave == 0) {
+      // 64 dwords that travel with the tile: the key indices of a gathered tile, or for a
+      // range tile 16 words of the offset bitmap (covering every offset of the 128 x 64
+      // tile) followed by the 2 words of the column bitmap
+      const int32_t* g;
+      if (T.idx != nullptr) {
+        g = T.idx + lane;
+      } else {
+        int wb = (P.off_max - (i0 - T.j0 + BQ - 1)) >> 5;          // first offset-bitmap word needed
+        g = reinterpret_cast<const int32_t*>(lane < 16 ? obits + wb + lane : cbits + (T.j0 >> 5) + (lane & 1));
+      }
+      __builtin_amdgcn_global_load_lds(g, (lds_void*)(stage + KTILE_B + VTILE_B), 4, 0, 0);
+    }
   };
   auto tile_wait = [&]() { __builtin_amdgcn_s_waitcnt(0x0f70); };   // vmcnt(0): this wave's direct loads have landed
 
@@ -244,8 +255,9 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
     if (MODE == 2 && T.kind == TK_RANGE) {
       // every key of the tile already belongs to a selected column: the
       // column pass has covered it, nothing is left for the range pass
-      uint32_t w0 = cbits[T.j0 >> 5], w1 = cbits[(T.j0 >> 5) + 1];
-      skip = skip || ((w0 & w1) == 0xFFFFFFFFu) || (T.rows <= 0);   // or the tile lies past the sequence end
+      // (the two column-bitmap words were staged with the tile)
+      const uint32_t* mw = reinterpret_cast<const uint32_t*>(stage + KTILE_B + VTILE_B);
+      skip = skip || ((mw[16] & mw[17]) == 0xFFFFFFFFu) || (T.rows <= 0);   // or the tile lies past the sequence end
     }
 
     if (!skip) {
@@ -297,18 +309,23 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
             }
         }
       } else if (MODE == 2 && T.kind == TK_RANGE) {
+        const uint32_t* mw = reinterpret_cast<const uint32_t*>(stage + KTILE_B + VTILE_B);
+        const int wb = (P.off_max - (i0 - T.j0 + BQ - 1)) >> 5;
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
           int tl = i_me - (T.j0 + 32 * sb + 8 * hf);
           int x0 = P.off_max - tl;                       // >= 0 by construction of the bitmap
-          uint32_t lo = obits[x0 >> 5], hi = obits[(x0 >> 5) + 1];
+          int k = (x0 >> 5) - wb;                        // 0 .. 8: word of the staged window
+          uint32_t lo = mw[k], hi = mw[k + 1];
           uint32_t ow = __builtin_amdgcn_alignbit(hi, lo, x0 & 31);  // bit b <-> offset tl - b
-          uint32_t cw = cbits[(T.j0 >> 5) + sb] >> (8 * hf);         // bit 16u+e <-> key is a selected column
+          uint32_t cw = mw[16 + sb] >> (8 * hf);                     // bit 16u+e <-> key is a selected column
           uint32_t km = ow & ~cw;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             int b = 16 * (r >> 3) + (r & 7);
-            s[sb][r] = ((km >> b) & 1u) ? s[sb][r] : ninf;
+            // all-ones where the pair is kept; then a bitwise select between score and -inf
+            uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(km, b, 1);
+            s[sb][r] = __uint_as_float((__float_as_uint(s[sb][r]) & keep) | (0xFF800000u & ~keep));
           }
         }
       }
