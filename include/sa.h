@@ -139,9 +139,9 @@ sa_status sa_select_strips(const sa_shape* shape,
  * out: out      [batch, n_q_heads, seq_len, head_dim], bf16 or fp32
  *      out_lse  (nullable) fp32 [batch*n_q_heads, seq_len], natural log of
  *               the masked sum-exp
- *      tiles    (nullable) uint64 [batch*n_q_heads]: number of 32x64
+ *      tiles    (nullable) uint64 [batch*n_q_heads]: number of 32x32
  *               (query rows x keys) score tiles the kernel computed for the
- *               head (one wave's unit of work: 4*head_dim*32*64 flop each)
+ *               head (one wave's unit of work: 4*head_dim*32*32 flop each)
  */
 sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
                          const int32_t* col_idx, const int32_t* col_cnt,

@@ -3,9 +3,10 @@
 // the merged column / slash / window mask (Eq. 3, Algorithm 1 last step).
 //
 // One workgroup = 4 waves = 128 query rows of one head; each wave owns 32
-// queries.  Keys are visited in tiles of 64.  For every tile the wave forms
-// S^T = K Q^T (keys x queries) with 32x32x16 bf16 MFMAs, so that one lane holds
-// scores of ONE query (lane % 32) for 16 keys per 32-key half tile: the
+// queries.  Keys are visited in tiles of 32 (small tiles and <= 168 registers
+// keep three workgroups, i.e. three waves per SIMD, resident).  For every tile the
+// wave forms S^T = K Q^T (keys x queries) with 32x32x16 bf16 MFMAs, so that one
+// lane holds scores of ONE query (lane % 32) for 16 keys of the tile: the
 // row-wise online softmax is then in-lane arithmetic plus a single exchange
 // between lanes l and l^32.  The probabilities, rounded to bf16, are directly
 // the B operand of O^T += V^T P^T, so the accumulators (O^T, head_dim x
@@ -20,15 +21,15 @@ namespace sa {
 namespace {
 
 constexpr int BQ = kFlashBQ;          // 128 query rows per workgroup
-constexpr int BK = kFlashBK;          // 64 keys per tile
+constexpr int BK = kFlashBK;          // 32 keys per tile
 constexpr int NT = 256;
 // LDS tiles are unpadded (the direct global->LDS loads write 1 KB runs); bank
 // conflicts are avoided by XOR-swizzling the 16-byte chunk index with the row.
 constexpr int KROW_B = 256;           // bytes per K row in LDS: 16 chunks, chunk c of row p stored at c ^ (p & 15)
-constexpr int VROW_B = 128;           // bytes per V^T row in LDS: 8 chunks, chunk c of row d stored at c ^ ((d >> 1) & 7)
+constexpr int VROW_B = 64;            // bytes per V^T row in LDS: 4 chunks, chunk c of row d stored at c ^ ((d >> 2) & 3)
 constexpr int KTILE_B = BK * KROW_B;
 constexpr int VTILE_B = kHeadDim * VROW_B;
-constexpr int IDX_B = BK * 4;
+constexpr int IDX_B = 256;            // 64 dwords that travel with a tile (key indices or mask words)
 constexpr int STAGE_B = KTILE_B + VTILE_B + IDX_B;
 constexpr float kLazy = 8.0f;         // rescale only when a row maximum grows by more than 2^8
 
@@ -52,7 +53,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 
 // MODE: 0 dense causal, 1 row log-sum-exp only (no V), 2 strip-masked sparse.
 template <int MODE, bool OUT_F32>
-__global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
+__global__ __launch_bounds__(NT, 3) void flash_kernel(FlashParams P) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr bool WITH_V = (MODE != 1);
 
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
   const uint32_t* obits = nullptr;
   const uint16_t* kc = nullptr;
   const uint16_t* vct = nullptr;
-  const int a64 = i0 / BK;   // index of the 64-key tile that holds row i0 (i0 % 128 == 0 in MODE 2)
+  const int a32 = i0 / BK;   // index of the 32-key tile that holds row i0 (i0 % 128 == 0 in MODE 2)
   if (MODE == 2) {
     cidx = P.col_idx_pad + (size_t)bh * P.cidx_stride;
     int cnt = min(max(P.col_cnt[bh], 0), S);
@@ -142,11 +143,11 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
     n_col_tiles = (lo + BK - 1) / BK;
     dl = P.dlist + (size_t)bh * P.dlist_stride;
     int dc = min(max(P.dcnt[bh], 0), P.dlist_stride);
-    // entries d of the ascending list with key tile a64 - d >= 0 ... d <= a64 + 1
+    // entries d of the ascending list whose key tile a32 + 3 - d is >= 0
     lo = 0; hi = dc;
     while (lo < hi) {
       int mid = (lo + hi) >> 1;
-      if (dl[mid] <= a64 + 1) lo = mid + 1; else hi = mid;
+      if (dl[mid] <= a32 + 3) lo = mid + 1; else hi = mid;
     }
     n_rng = lo;
     cbits = P.col_bits + (size_t)bh * P.cb_words;
@@ -171,9 +172,9 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
     } else {
       int j0;
       if (MODE == 2) {
-        // d = (64-key tile of row i0 + 1) - key tile; walk from far to near
+        // tile diagonal d <-> key tile a32 + 3 - d; walk from far to near
         int d = dl[n_rng - 1 - (t - n_col_tiles)];
-        j0 = (a64 + 1 - d) * BK;
+        j0 = (a32 + 3 - d) * BK;
         T.kind = TK_RANGE;
       } else {
         j0 = t * BK;
@@ -193,24 +194,24 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
 
   // Staging of one tile with direct global -> LDS loads (no registers in between).
   // One wave instruction writes a 1 KB run of LDS, lane l its bytes [16 l, 16 l + 16):
-  // for K that is 4 physical rows, for V^T 8 rows.  Each lane therefore fetches the
+  // for K that is 4 physical rows, for V^T 16 rows.  Each lane therefore fetches the
   // global chunk that belongs at its LDS position: the K row whose slot it is (bits 2
   // and 3 of the row index exchanged, see krow_slot) and the chunk that the XOR
-  // swizzle maps there.  Wave w issues runs w, w+4, w+8, w+12 of either tile.
-  int koff[4], voff[4];
+  // swizzle maps there.  Wave w issues runs w and w+4 of either tile.
+  int koff[2], voff[2];
 #pragma unroll
-  for (int n = 0; n < 4; ++n) {
+  for (int n = 0; n < 2; ++n) {
     int run = wave + 4 * n;
     int p = 4 * run + (lane >> 4);                 // physical K row
     int c = (lane & 15) ^ (p & 15);                // logical 16-byte chunk stored there
     koff[n] = (krow_slot(p) << 16) | (c * 8);      // key row within the tile, element offset in the row
-    int d = 8 * run + (lane >> 3);                 // V^T row
-    int cv = (lane & 7) ^ ((d >> 1) & 7);
+    int d = 16 * run + (lane >> 2);                // V^T row
+    int cv = (lane & 3) ^ ((d >> 2) & 3);
     voff[n] = (d << 16) | (cv * 8);
   }
   auto tile_dma = [&](const Tile& T, char* stage) {
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
+    for (int n = 0; n < 2; ++n) {
       int run = wave + 4 * n;
       int row = min(T.krow0 + (koff[n] >> 16), T.kmax);
       const uint16_t* g = T.kb + (size_t)row * kHeadDim + (koff[n] & 0xFFFF);
@@ -218,22 +219,22 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
     }
     if (WITH_V) {
 #pragma unroll
-      for (int n = 0; n < 4; ++n) {
+      for (int n = 0; n < 2; ++n) {
         int run = wave + 4 * n;
         const uint16_t* g = T.vt + (size_t)(voff[n] >> 16) * T.vt_stride + (voff[n] & 0xFFFF);
         __builtin_amdgcn_global_load_lds(g, (lds_void*)(stage + KTILE_B + 1024 * run), 16, 0, 0);
       }
     }
     if (MODE == 2 && wave == 0) {
-      // 64 dwords that travel with the tile: the key indices of a gathered tile, or for a
-      // range tile 16 words of the offset bitmap (covering every offset of the 128 x 64
-      // tile) followed by the 2 words of the column bitmap
+      // 64 dwords that travel with the tile: the key indices of a gathered tile (32, twice),
+      // or for a range tile 16 words of the offset bitmap (covering every offset of the
+      // 128 x 32 tile) followed by the word of the column bitmap
       const int32_t* g;
       if (T.idx != nullptr) {
-        g = T.idx + lane;
+        g = T.idx + (lane & 31);
       } else {
         int wb = (P.off_max - (i0 - T.j0 + BQ - 1)) >> 5;          // first offset-bitmap word needed
-        g = reinterpret_cast<const int32_t*>(lane < 16 ? obits + wb + lane : cbits + (T.j0 >> 5) + (lane & 1));
+        g = reinterpret_cast<const int32_t*>(lane < 16 ? obits + wb + lane : cbits + (T.j0 >> 5));
       }
       __builtin_amdgcn_global_load_lds(g, (lds_void*)(stage + KTILE_B + VTILE_B), 4, 0, 0);
     }
@@ -257,85 +258,73 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
       // column pass has covered it, nothing is left for the range pass
       // (the two column-bitmap words were staged with the tile)
       const uint32_t* mw = reinterpret_cast<const uint32_t*>(stage + KTILE_B + VTILE_B);
-      skip = skip || ((mw[16] & mw[17]) == 0xFFFFFFFFu) || (T.rows <= 0);   // or the tile lies past the sequence end
+      skip = skip || (mw[16] == 0xFFFFFFFFu) || (T.rows <= 0);   // or the tile lies past the sequence end
     }
 
     if (!skip) {
       ++tiles_done;
-      // ---- S^T = K Q^T for the two 32-key halves ----------------------------
-      f32x16 s[2];
+      // ---- S^T = K Q^T ----------------------------------------------------------
+      f32x16 s;
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
-        // row p = 32 sb + ql; logical chunk 2 ks + hf lives at physical chunk (2 ks + hf) ^ (p & 15)
-        const char* kp = stage + (32 * sb + ql) * KROW_B;
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+      {
+        // row p = ql; logical chunk 2 ks + hf lives at physical chunk (2 ks + hf) ^ (p & 15)
+        const char* kp = stage + ql * KROW_B;
         const int ksw = ql & 15;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
           bf16x8 kf = as_bf16x8(*reinterpret_cast<const uint4*>(kp + (((2 * ks + hf) ^ ksw) << 4)));
-          s[sb] = mfma_32x32x16(kf, qf[ks], s[sb]);
+          s = mfma_32x32x16(kf, qf[ks], s);
         }
       }
-      // element r of s[sb] is key  j0 + 32*sb + 16*(r/8) + 8*hf + r%8  vs query i_me
+      // element r of s is key  j0 + 16*(r/8) + 8*hf + r%8  vs query i_me
 
       // ---- mask ---------------------------------------------------------------
       const float ninf = -__builtin_inff();
       if (T.kind == TK_CAUSAL) {
         if (T.j0 + BK - 1 > iw0) {
+          int tl = i_me - (T.j0 + 8 * hf);   // keep bit b iff b <= tl
 #pragma unroll
-          for (int sb = 0; sb < 2; ++sb) {
-            int tl = i_me - (T.j0 + 32 * sb + 8 * hf);   // keep bit b iff b <= tl
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              int b = 16 * (r >> 3) + (r & 7);
-              s[sb][r] = (b <= tl) ? s[sb][r] : ninf;
-            }
+          for (int r = 0; r < 16; ++r) {
+            int b = 16 * (r >> 3) + (r & 7);
+            s[r] = (b <= tl) ? s[r] : ninf;
           }
         }
       } else if (MODE == 2 && T.kind == TK_COLIDX) {
         const int32_t* il = reinterpret_cast<const int32_t*>(stage + KTILE_B + VTILE_B);
         if (il[BK - 1] > iw0) {
 #pragma unroll
-          for (int sb = 0; sb < 2; ++sb)
+          for (int u = 0; u < 2; ++u) {
+            const int4* ip = reinterpret_cast<const int4*>(il + 16 * u + 8 * hf);
+            int4 x0 = ip[0], x1 = ip[1];
+            int jj[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-              const int4* ip = reinterpret_cast<const int4*>(il + 32 * sb + 16 * u + 8 * hf);
-              int4 x0 = ip[0], x1 = ip[1];
-              int jj[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-#pragma unroll
-              for (int e = 0; e < 8; ++e)
-                s[sb][8 * u + e] = (jj[e] <= i_me) ? s[sb][8 * u + e] : ninf;
-            }
+            for (int e = 0; e < 8; ++e) s[8 * u + e] = (jj[e] <= i_me) ? s[8 * u + e] : ninf;
+          }
         }
       } else if (MODE == 2 && T.kind == TK_RANGE) {
         const uint32_t* mw = reinterpret_cast<const uint32_t*>(stage + KTILE_B + VTILE_B);
         const int wb = (P.off_max - (i0 - T.j0 + BQ - 1)) >> 5;
+        int tl = i_me - (T.j0 + 8 * hf);
+        int x0 = P.off_max - tl;                       // >= 0 by construction of the bitmap
+        int k = (x0 >> 5) - wb;                        // word of the staged window
+        uint32_t lo = mw[k], hi = mw[k + 1];
+        uint32_t ow = __builtin_amdgcn_alignbit(hi, lo, x0 & 31);  // bit b <-> offset tl - b
+        uint32_t cw = mw[16] >> (8 * hf);                          // bit 16u+e <-> key is a selected column
+        uint32_t km = ow & ~cw;
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-          int tl = i_me - (T.j0 + 32 * sb + 8 * hf);
-          int x0 = P.off_max - tl;                       // >= 0 by construction of the bitmap
-          int k = (x0 >> 5) - wb;                        // 0 .. 8: word of the staged window
-          uint32_t lo = mw[k], hi = mw[k + 1];
-          uint32_t ow = __builtin_amdgcn_alignbit(hi, lo, x0 & 31);  // bit b <-> offset tl - b
-          uint32_t cw = mw[16 + sb] >> (8 * hf);                     // bit 16u+e <-> key is a selected column
-          uint32_t km = ow & ~cw;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            int b = 16 * (r >> 3) + (r & 7);
-            // all-ones where the pair is kept; then a bitwise select between score and -inf
-            uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(km, b, 1);
-            s[sb][r] = __uint_as_float((__float_as_uint(s[sb][r]) & keep) | (0xFF800000u & ~keep));
-          }
+        for (int r = 0; r < 16; ++r) {
+          int b = 16 * (r >> 3) + (r & 7);
+          // all-ones where the pair is kept; then a bitwise select between score and -inf
+          uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(km, b, 1);
+          s[r] = __uint_as_float((__float_as_uint(s[r]) & keep) | (0xFF800000u & ~keep));
         }
       }
 
       // ---- online softmax (one query per lane) -------------------------------
-      float mx = s[0][0];
+      float mx = s[0];
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
       mx = fmaxf(mx, swap_half(mx));
       // lazy rescale: keep the old reference maximum unless it grew by more than
       // 2^kLazy (probabilities then stay <= 2^kLazy, exact in fp32 and bf16 alike)
@@ -354,37 +343,34 @@ __global__ __launch_bounds__(NT, 2) void flash_kernel(FlashParams P) {
         }
       }
       float rs = 0.f;
-      uint32_t pk[2][8];
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb) {
+      uint32_t pk[8];
+      {
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_run));
+          p[r] = fast_exp2(fmaf(s[r], c2, -m_run));
           rs += p[r];
         }
 #pragma unroll
-        for (int r = 0; r < 8; ++r) pk[sb][r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
+        for (int r = 0; r < 8; ++r) pk[r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
       }
       l_run += rs;
 
       if (WITH_V) {
         // ---- O^T += V^T P^T ---------------------------------------------------
-        // row d = 32 mb + ql; logical chunk 4 sb + 2 u + hf lives at physical chunk (..) ^ ((d >> 1) & 7)
+        // row d = 32 mb + ql; logical chunk 2 u + hf lives at physical chunk (2 u + hf) ^ ((d >> 2) & 3)
         const char* vp = stage + KTILE_B + ql * VROW_B;
-        const int vsw = (ql >> 1) & 7;
+        const int vsw = (ql >> 2) & 3;
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
+        for (int u = 0; u < 2; ++u) {
+          uint4 pw = {pk[4 * u], pk[4 * u + 1], pk[4 * u + 2], pk[4 * u + 3]};
+          bf16x8 pb = as_bf16x8(pw);
 #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            uint4 pw = {pk[sb][4 * u], pk[sb][4 * u + 1], pk[sb][4 * u + 2], pk[sb][4 * u + 3]};
-            bf16x8 pb = as_bf16x8(pw);
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
-              bf16x8 vf = as_bf16x8(*reinterpret_cast<const uint4*>(vp + mb * 32 * VROW_B + (((4 * sb + 2 * u + hf) ^ vsw) << 4)));
-              o[mb] = mfma_32x32x16(vf, pb, o[mb]);
-            }
+          for (int mb = 0; mb < 4; ++mb) {
+            bf16x8 vf = as_bf16x8(*reinterpret_cast<const uint4*>(vp + mb * 32 * VROW_B + (((2 * u + hf) ^ vsw) << 4)));
+            o[mb] = mfma_32x32x16(vf, pb, o[mb]);
           }
+        }
       }
     }
 

@@ -69,8 +69,8 @@ struct SparseWs {
 SparseWs sparse_ws(const Dims& d) {
   SparseWs w;
   w.cb_words = d.S_pad / 32 + 2;
-  w.rb_words = d.S_pad / 32 + 8;
-  w.dlist_stride = d.S_pad / 64 + 2;
+  w.rb_words = d.S_pad / 32 + 24;
+  w.dlist_stride = d.S_pad / 32 + 8;
   w.off_max = d.S_pad - 1;
   size_t at = 0;
   w.vt = at;    at += align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2);
