@@ -9,7 +9,7 @@ with the inputs already resident in HBM.  Prints ONE JSON line:
           workload named in config.workload (default: the S=128K ChatGLM3-6B-
           shaped config, alpha = 0.95, literal generator constants)
   roofline      the strip-masked flash kernel against the bf16 MFMA peak:
-                4*d*(computed 32x32 tiles) flop / mean kernel duration taken
+                4*d*(computed 32x64 tiles) flop / mean kernel duration taken
                 from HIP events the library records around the launch, on the
                 launch stream, inside the timed region
   cpu_baseline  the fp64 oracle timed on this host on a bounded sample of the
@@ -34,7 +34,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
-TILE_FLOP = 4 * 128 * 32 * 32   # QK^T + PV of one 32x32 (query rows x keys) score tile at d = 128
+TILE_FLOP = 4 * 128 * 32 * 64   # QK^T + PV of one 32x64 (query rows x keys) score tile at d = 128
 
 
 def log(msg: str) -> None:
@@ -179,7 +179,7 @@ def main() -> int:
     flop = float(tiles.sum()) * TILE_FLOP
     achieved = flop / (flash_ms * 1e-3) / 1e12
     # tiles a dense causal sweep computes: every 32-row block against the key tiles up to its last row
-    dense_tiles = sum((b + 1) for b in range((S + 31) // 32)) * Hq
+    dense_tiles = sum(((32 * b + 31) // 64 + 1) for b in range((S + 31) // 32)) * Hq
     cc = plan.col_cnt.cpu().numpy()
     sc = plan.slash_cnt.cpu().numpy()
     ci = plan.col_idx[0, :int(cc[0])].cpu().numpy()

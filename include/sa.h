@@ -50,7 +50,8 @@ typedef enum {
 } sa_status;
 
 /* Problem shape.  head_dim must be 128 and causal must be 1 (the method is
- * defined for decoder-only prefill); n_q_heads % n_kv_heads == 0. */
+ * defined for decoder-only prefill); n_q_heads % n_kv_heads == 0;
+ * seq_len <= 2^24 and batch * n_q_heads <= 65535 (else SA_ERR_UNSUPPORTED). */
 typedef struct {
   int32_t batch;
   int32_t n_q_heads;
@@ -139,9 +140,9 @@ sa_status sa_select_strips(const sa_shape* shape,
  * out: out      [batch, n_q_heads, seq_len, head_dim], bf16 or fp32
  *      out_lse  (nullable) fp32 [batch*n_q_heads, seq_len], natural log of
  *               the masked sum-exp
- *      tiles    (nullable) uint64 [batch*n_q_heads]: number of 32x32
+ *      tiles    (nullable) uint64 [batch*n_q_heads]: number of 32x64
  *               (query rows x keys) score tiles the kernel computed for the
- *               head (one wave's unit of work: 4*head_dim*32*32 flop each)
+ *               head (one wave's unit of work: 4*head_dim*32*64 flop each)
  */
 sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
                          const int32_t* col_idx, const int32_t* col_cnt,

@@ -31,6 +31,26 @@ __device__ __forceinline__ float swap_half(float x) {
   return __shfl_xor(x, 32, 64);
 }
 
+// Lanes l and l^32 each hold x; both receive the pair (x of the lower lane, x of the
+// upper lane) through one register swap between the two 32-lane halves: a vector-ALU
+// operation, no trip through LDS.
+__device__ __forceinline__ void half_pair(float x, float& lo, float& hi) {
+  unsigned u = __float_as_uint(x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  lo = __uint_as_float(r[0]);
+  hi = __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float half_max(float x) {
+  float a, b;
+  half_pair(x, a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float half_sum(float x) {
+  float a, b;
+  half_pair(x, a, b);
+  return a + b;
+}
+
 // round-to-nearest-even fp32 -> bf16 pair packed into one dword (lo = a)
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;

@@ -7,7 +7,7 @@ namespace sa {
 
 constexpr int kHeadDim = 128;  // the only supported head dimension
 constexpr int kFlashBQ = 128;  // query rows per workgroup of the flash kernels
-constexpr int kFlashBK = 32;   // keys per tile
+constexpr int kFlashBK = 64;   // keys per tile
 
 struct FlashParams {
   const uint16_t* q;        // [n_bh, S, 128] bf16
