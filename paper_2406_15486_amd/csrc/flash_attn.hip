@@ -2,8 +2,9 @@
 // row log-sum-exp of the sampled queries (stage 1, pass 1) and attention under
 // the merged column / slash / window mask (Eq. 3, Algorithm 1 last step).
 //
-// A wave owns 32 query rows.  Keys are visited in tiles of 64.  For every tile
-// the wave forms S^T = K Q^T (keys x queries) with 32x32x16 bf16 MFMAs, so that
+// A workgroup owns 256 query rows of one head; each of its 8 waves owns 32 of
+// them.  Keys are visited in tiles of 64, one K/V stream per workgroup.  For every
+// tile a wave forms S^T = K Q^T (keys x queries) with 32x32x16 bf16 MFMAs, so that
 // one lane holds scores of ONE query (lane % 32) for 16 keys per 32-key half
 // tile: the row-wise online softmax is then in-lane arithmetic plus a single
 // exchange between lanes l and l^32.  The probabilities, rounded to bf16, are
@@ -12,15 +13,16 @@
 // K tiles live in LDS as [key][d]; V is read from a pre-transposed copy
 // (V^T, [d][key]) so both MFMA A operands are 16-byte LDS reads.
 //
-// Schedule.  A workgroup is two groups of four waves; each group owns one
-// 128-row query tile (two neighbouring tiles of one head) with its own K/V
-// stream.  Waves w and w+4 share a SIMD.  Left alone, two waves that alternate
-// an MFMA section and a vector-ALU (softmax) section fall into step - both on
-// the matrix pipe, then both on the vector pipe - and each pipe idles half the
-// time.  Here the groups are held one phase apart by two workgroup barriers per
-// tile: while group 0 does the softmax of its tile t, group 1 issues the MFMAs of
-// P V(t-1) and K Q^T(t), and vice versa, so every SIMD always has one wave
-// feeding the matrix pipe and one feeding the vector pipe.
+// Schedule.  The waves form two groups of four (rows 0..127 and 128..255); waves
+// w and w+4 share a SIMD.  Left alone, two waves that alternate an MFMA section
+// and a vector-ALU (softmax) section fall into step - both on the matrix pipe,
+// then both on the vector pipe - and each pipe idles half the time.  Here the
+// groups are held one phase apart by two workgroup barriers per tile: while group
+// 0 does the softmax of tile t, group 1 issues the MFMAs of P V(t-1) and
+// K Q^T(t), and vice versa, so every SIMD always has one wave feeding the matrix
+// pipe and one feeding the vector pipe.  Both groups read the same K/V tiles,
+// which therefore stay in LDS for two phases; four stages of each are resident,
+// filled by direct global->LDS loads two and three tiles ahead.
 #include "sa_device.h"
 #include "sa_kernels.h"
 
@@ -28,9 +30,11 @@ namespace sa {
 
 namespace {
 
-constexpr int BQ = kFlashBQ;          // 128 query rows per group
+constexpr int BQ = kFlashBQ;          // 256 query rows per workgroup
 constexpr int BK = kFlashBK;          // 64 keys per tile
 constexpr int NT = 512;               // two groups of four waves
+constexpr int NSTAGE = 4;             // K and V^T tiles resident in LDS
+constexpr int NAUX = 8;               // ring of aux-word slots
 // LDS tiles are unpadded (the direct global->LDS loads write 1 KB runs); bank
 // conflicts are avoided by XOR-swizzling the 16-byte chunk index with the row.
 constexpr int KROW_B = 256;           // bytes per K row in LDS: 16 chunks, chunk c of row p stored at c ^ (p & 15)
@@ -38,31 +42,15 @@ constexpr int VROW_B = 128;           // bytes per V^T row in LDS: 8 chunks, chu
 constexpr int KTILE_B = BK * KROW_B;
 constexpr int VTILE_B = kHeadDim * VROW_B;
 constexpr int AUX_B = 256;            // 64 dwords per tile: key indices or mask words
-constexpr int OFF_K = 0;                       // per group: K tiles, double buffered
-constexpr int OFF_V = 2 * KTILE_B;             //            V^T tiles, double buffered
-constexpr int OFF_A = OFF_V + 2 * VTILE_B;     //            aux words, ring of four
-constexpr int GROUP_B = OFF_A + 4 * AUX_B;     // 66560 bytes per group
+constexpr int OFF_K = 0;
+constexpr int OFF_V = OFF_K + NSTAGE * KTILE_B;
+constexpr int OFF_A = OFF_V + NSTAGE * VTILE_B;
+constexpr int OFF_DUMP = OFF_A + NAUX * AUX_B;      // 1 KB per wave: where loads of tiles past the end go
+constexpr int LDS_B = OFF_DUMP + 8 * 1024;          // 141312 bytes
 constexpr float kLazy = 8.0f;         // rescale only when a row maximum grows by more than 2^8
 
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
 
-struct Tile {
-  const uint16_t* kb;   // K array the tile's rows come from (row stride 128 elements)
-  const uint16_t* vt;   // &V^T[0][first key] (row stride S_pad elements)
-  const int32_t* idx;   // key index of each of the 64 rows (TK_COLIDX) or null
-  int krow0;            // first row of the tile in kb
-  int kmax;             // last row of kb that may be read (rows past it are clamped: they are masked anyway)
-  int j0;               // first key index (contiguous tiles)
-  int kind;
-};
-
-// Direct global -> LDS load: lane l of the wave moves N bytes from global address
-// `base` + `off` (base wave-uniform, in scalar registers; off per lane) to LDS
-// address `lds` + N * l (`lds` wave-uniform, passed in M0).  It is written as inline
-// assembly so that the waits on it are the explicit vm_wait calls below: the
-// compiler, when it issues this instruction itself, makes every later LDS read wait
-// for all of them (it cannot tell the buffers apart), which serialises the prefetch
-// of tile t+1 with the arithmetic on tile t.  The loads of a wave complete in order.
 // a wave-uniform pointer, forced into scalar registers
 __device__ __forceinline__ uint64_t scalar_ptr(const void* p) {
   const uint64_t v = reinterpret_cast<uint64_t>(p);
@@ -70,6 +58,13 @@ __device__ __forceinline__ uint64_t scalar_ptr(const void* p) {
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
   return ((uint64_t)hi << 32) | lo;
 }
+// Direct global -> LDS load: lane l of the wave moves N bytes from global address
+// `base` + `off` (base wave-uniform, in scalar registers; off per lane) to LDS
+// address `lds` + N * l (`lds` wave-uniform, passed in M0).  It is written as inline
+// assembly so that the waits on it are the explicit vm_wait calls below: the
+// compiler, when it issues this instruction itself, makes every later LDS read wait
+// for all of them (it cannot tell the buffers apart), which serialises the prefetch
+// with the arithmetic.  The loads of a wave complete in order.
 __device__ __forceinline__ void dma16(uint64_t base, uint32_t off, uint32_t lds) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds)
                : "memory", "m0");
@@ -97,23 +92,19 @@ __device__ __forceinline__ void wg_barrier() {
 // MODE: 0 dense causal, 1 row log-sum-exp only (no V), 2 strip-masked sparse.
 template <int MODE, bool OUT_F32>
 __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
-  extern __shared__ __attribute__((aligned(16))) char smem_all[];
+  extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr bool WITH_V = (MODE != 1);
 
   const int tid = threadIdx.x;
-  const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
-  const int grp = wave8 >> 2;          // phase group
-  const int wave = wave8 & 3;          // wave within the group
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..7, wave-uniform, kept in an SGPR
+  const int grp = wave >> 2;           // phase group
   const int lane = tid & 63;
   const int ql = lane & 31;   // query within the wave / row within a 32-row operand
   const int hf = lane >> 5;   // which half of the contraction block this lane feeds
-  char* smem = smem_all + grp * GROUP_B;
-  const uint32_t smem_lds = __builtin_amdgcn_readfirstlane(
-      (int)(uintptr_t)(__attribute__((address_space(3))) char*)smem_all + grp * GROUP_B);
+  const uint32_t smem_lds = __builtin_amdgcn_readfirstlane((int)(uintptr_t)(__attribute__((address_space(3))) char*)smem);
 
-  // ---- which head and pair of query tiles this workgroup owns ----------------
-  const int n_pairs = (P.n_qtiles + 1) >> 1;
-  int bh, ap;
+  // ---- which (head, query tile) this workgroup owns ------------------------
+  int bh, a;
   {
     const int bid = blockIdx.x;
     if (MODE == 2) {
@@ -123,89 +114,78 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       // a working set (tens of MB per XCD) that the memory-side cache can hold.
       if (P.n_bh >= 8) {
         int xcd = bid & 7, slot = bid >> 3;
-        ap = n_pairs - 1 - slot % n_pairs;
-        bh = xcd + 8 * (slot / n_pairs);
+        a = P.n_qtiles - 1 - slot % P.n_qtiles;
+        bh = xcd + 8 * (slot / P.n_qtiles);
         if (bh >= P.n_bh) return;
       } else {
-        ap = n_pairs - 1 - bid / P.n_bh;
+        a = P.n_qtiles - 1 - bid / P.n_bh;
         bh = bid % P.n_bh;
-        if (ap < 0) return;
+        if (a < 0) return;
       }
     } else {
-      // a bundle = the query heads sharing one KV head at one pair of query tiles; the
+      // a bundle = the query heads sharing one KV head at one query tile; the
       // bundle's workgroups land on one XCD so the K/V stream is shared in L2.
       int xcd = bid & 7, slot = bid >> 3;
       int bl = slot / P.group, hg = slot % P.group;
       int bundle = bl * 8 + xcd;
-      if (bundle >= n_pairs * P.n_bkv) return;
-      ap = n_pairs - 1 - bundle / P.n_bkv;
+      if (bundle >= P.n_qtiles * P.n_bkv) return;
+      a = P.n_qtiles - 1 - bundle / P.n_bkv;
       int bkv = bundle % P.n_bkv;
       bh = bkv * P.group + hg;
     }
   }
   const int bkv = bh / P.group;
   const int S = P.S;
+  const int i0 = P.q_row0 + a * BQ;                     // first query row of the workgroup
+  const int i_last_wg = min(i0 + BQ, P.q_row0 + P.n_qrows) - 1;  // last valid row
+  const int iw0 = i0 + 32 * wave;                        // first query row of the wave
+  const int i_me = iw0 + ql;                             // this lane's query row
+  const bool row_ok = i_me <= i_last_wg;
+  const int a64 = i0 / BK;   // index of the 64-key tile that holds row i0 (i0 % 256 == 0 in MODE 2)
   const uint16_t* kbase = P.k + (size_t)bkv * S * kHeadDim;
   const uint16_t* vtbase = WITH_V ? P.vt + (size_t)bkv * kHeadDim * P.S_pad : nullptr;
+
+  // ---- tile schedule: gathered-column tiles, then range tiles (sparse), or the
+  //      causal sweep (dense / log-sum-exp) ------------------------------------------
   const int32_t* cidx = nullptr;
   const int32_t* dl = nullptr;
   const uint32_t* cbits = nullptr;
   const uint32_t* obits = nullptr;
-  int col_cnt = 0, d_cnt = 0;
+  const uint16_t* kc = nullptr;
+  const uint16_t* vct = nullptr;
+  int n_col_tiles = 0, n_rng = 0;
   if (MODE == 2) {
     cidx = P.col_idx_pad + (size_t)bh * P.cidx_stride;
-    col_cnt = min(max(P.col_cnt[bh], 0), S);
+    int cnt = min(max(P.col_cnt[bh], 0), S);
+    int lo = 0, hi = cnt;          // selected columns j <= last row of the tile (ascending list)
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (cidx[mid] <= i_last_wg) lo = mid + 1; else hi = mid;
+    }
+    n_col_tiles = (lo + BK - 1) / BK;
     dl = P.dlist + (size_t)bh * P.dlist_stride;
-    d_cnt = min(max(P.dcnt[bh], 0), P.dlist_stride);
+    int dc = min(max(P.dcnt[bh], 0), P.dlist_stride);
+    lo = 0; hi = dc;               // tile diagonals d whose key tile a64 + 3 - d is >= 0
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (dl[mid] <= a64 + 3) lo = mid + 1; else hi = mid;
+    }
+    n_rng = lo;
     cbits = P.col_bits + (size_t)bh * P.cb_words;
     obits = P.off_bits + (size_t)bh * P.rb_words;
+    kc = P.kc + (size_t)bh * P.S_pad * kHeadDim;
+    vct = P.vct + (size_t)bh * kHeadDim * P.S_pad;
   }
-
-  // tile schedule of query tile `qt`: gathered-column tiles, then range tiles
-  // (sparse), or the causal sweep (dense / log-sum-exp)
-  auto schedule = [&](int qt, int& nct, int& nrg) -> int {
-    nct = 0; nrg = 0;
-    if (qt >= P.n_qtiles) return 0;
-    const int first = P.q_row0 + qt * BQ;
-    const int last = min(first + BQ, P.q_row0 + P.n_qrows) - 1;
-    if (MODE == 2) {
-      int lo = 0, hi = col_cnt;      // selected columns j <= last row of the tile (ascending list)
-      while (lo < hi) {
-        int mid = (lo + hi) >> 1;
-        if (cidx[mid] <= last) lo = mid + 1; else hi = mid;
-      }
-      nct = (lo + BK - 1) / BK;
-      lo = 0; hi = d_cnt;            // tile diagonals d with key tile first/64 + 1 - d >= 0
-      while (lo < hi) {
-        int mid = (lo + hi) >> 1;
-        if (dl[mid] <= first / BK + 1) lo = mid + 1; else hi = mid;
-      }
-      nrg = lo;
-      return nct + nrg;
-    }
-    return min(last, S - 1) / BK + 1;
-  };
-  const int a = 2 * ap + (1 - grp);          // group 0 takes the later (heavier) tile of the pair
-  int n_col_tiles, n_rng, pn_col, pn_rng;
-  const int n_tiles = __builtin_amdgcn_readfirstlane(schedule(a, n_col_tiles, n_rng));
-  const int n_partner = schedule(2 * ap + grp, pn_col, pn_rng);
-  const int n_iter = __builtin_amdgcn_readfirstlane(max(n_tiles, n_partner));   // both groups pass the same barriers
   n_col_tiles = __builtin_amdgcn_readfirstlane(n_col_tiles);
   n_rng = __builtin_amdgcn_readfirstlane(n_rng);
-
-  const int i0 = P.q_row0 + a * BQ;                     // first query row of the group
-  const int i_last_g = min(i0 + BQ, P.q_row0 + P.n_qrows) - 1;   // last valid row (< i0 for an empty group)
-  const int iw0 = i0 + 32 * wave;                        // first query row of the wave
-  const int i_me = iw0 + ql;                             // this lane's query row
-  const bool row_ok = i_me <= i_last_g;
-  const int a64 = i0 / BK;   // index of the 64-key tile that holds row i0 (i0 % 128 == 0 in MODE 2)
-  const uint16_t* kc = (MODE == 2) ? P.kc + (size_t)bh * P.S_pad * kHeadDim : nullptr;
-  const uint16_t* vct = (MODE == 2) ? P.vct + (size_t)bh * kHeadDim * P.S_pad : nullptr;
+  const int n_tiles = __builtin_amdgcn_readfirstlane(
+      (MODE == 2) ? (n_col_tiles + n_rng) : (min(i_last_wg, S - 1) / BK + 1));
 
   // Descriptor of tile t.  A range tile is named by its tile diagonal d: key tile
-  // a64 + 1 - d.  The d values come from a list in global memory; they are fetched
-  // (fetch_d) two tiles ahead of their first use and handed on in scalar registers,
-  // so that no phase waits on a scalar load.
+  // a64 + 3 - d, which the 256 rows meet at offsets [64 d - 255, 64 d + 63].  The d
+  // values come from a list in global memory; they are fetched (fetch_d) four tiles
+  // ahead of their first use and handed on in scalar registers, so that no phase
+  // waits on a scalar load.
   auto fetch_d = [&](int t) -> int {
     // read through the constant address space: the list is not written while the kernel
     // runs, and only so does the load stay a scalar one (tracked apart from the vector
@@ -215,39 +195,20 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       return ((const_i32_ptr)(uintptr_t)dl)[n_rng - 1 - (t - n_col_tiles)];   // far to near
     return 0;
   };
-  auto get_tile = [&](int t, int d) -> Tile {
-    Tile T;
-    if (MODE == 2 && t < n_col_tiles) {
-      T.kb = kc;
-      T.krow0 = t * BK;
-      T.kmax = P.S_pad - 1;
-      T.vt = vct + t * BK;
-      T.idx = cidx + t * BK;
-      T.j0 = 0;
-      T.kind = TK_COLIDX;
-    } else {
-      int j0;
-      if (MODE == 2) {
-        j0 = (a64 + 1 - d) * BK;
-        T.kind = TK_RANGE;
-      } else {
-        j0 = t * BK;
-        T.kind = (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
-      }
-      T.kb = kbase;
-      T.krow0 = j0;
-      T.kmax = S - 1;
-      T.vt = WITH_V ? vtbase + j0 : nullptr;
-      T.idx = nullptr;
-      T.j0 = j0;
-    }
-    return T;
+  // kind and first key of tile t (wave-uniform; no memory access)
+  auto is_col = [&](int t) -> bool { return MODE == 2 && t < n_col_tiles; };
+  auto first_key = [&](int t, int d) -> int {          // contiguous tiles only
+    return (MODE == 2) ? (a64 + 3 - d) * BK : t * BK;
   };
+  // array bases as scalars, once
+  const uint64_t s_kbase = scalar_ptr(kbase), s_vtbase = scalar_ptr(vtbase);
+  const uint64_t s_kc = scalar_ptr(kc), s_vct = scalar_ptr(vct), s_cidx = scalar_ptr(cidx);
+  const uint64_t s_cbits = scalar_ptr(cbits), s_obits = scalar_ptr(obits);
 
   // ---- Q^T operand: 8 contraction steps of 16, resident in registers -------
   bf16x8 qf[8];
   {
-    int qr = row_ok ? i_me : max(min(i_last_g, S - 1), 0);
+    int qr = row_ok ? i_me : max(min(i_last_wg, S - 1), 0);
     const uint16_t* qrow = P.q + ((size_t)bh * S + qr) * kHeadDim;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
@@ -268,11 +229,11 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   // for K that is 4 physical rows, for V^T 8 rows.  Each lane therefore fetches the
   // global chunk that belongs at its LDS position: the K row whose slot it is (bits 2
   // and 3 of the row index exchanged, see krow_slot) and the chunk that the XOR
-  // swizzle maps there.  Wave w of the group issues runs w, w+4, w+8, w+12.
-  // The lane's byte offset inside a run is fixed for the whole kernel, and run n of
-  // a wave lies a constant 16 K rows / 32 V^T rows after run 0 (neither the swizzle
-  // nor the slot permutation sees that step): per tile and per load only the scalar
-  // base address changes, so issuing a tile costs no vector arithmetic.
+  // swizzle maps there.  A tile is 16 runs of K and 16 of V^T; wave w issues runs w
+  // and w + 8 of each.  The lane's byte offset inside a run is fixed for the whole
+  // kernel, and run w + 8 lies a constant 32 K rows / 64 V^T rows after run w
+  // (neither the swizzle nor the slot permutation sees that step): per tile and per
+  // load only the scalar base address changes, so issuing costs no vector arithmetic.
   uint32_t koff0, voff0;
   {
     int p = 4 * wave + (lane >> 4);                // physical K row of run `wave`
@@ -282,85 +243,109 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     int cv = (lane & 7) ^ ((d >> 1) & 7);
     voff0 = (uint32_t)d * (uint32_t)P.S_pad * 2u + cv * 16;
   }
-  // The 4 loads of a V^T tile and the 4 of a K tile are issued one at a time
-  // (load_v_one / load_k_one), so the callers can spread them between their other
-  // instructions: a wave that issues them back to back stalls ~40 cycles on each.
-  bool ld_v_on = false, ld_k_on = false;
-  uint64_t ld_vbase = 0, ld_kbase = 0;
-  uint32_t ld_vdst = 0, ld_kdst = 0, ld_klim = 0;
-  auto load_v_begin = [&](int t, int d, bool on) {
-    ld_v_on = WITH_V && on;
-    if (ld_v_on) {
-      const Tile T = get_tile(t, d);
-      ld_vbase = scalar_ptr(T.vt);
-      ld_vdst = smem_lds + OFF_V + (t & 1) * VTILE_B + 1024 * wave;
-    }
+  // The loads are issued one at a time (load_v_one / load_k_one, n = 0, 1), so the
+  // caller can spread them between its MFMAs: a wave that issues them back to back
+  // stalls on each.  Loads of a tile past the end of the schedule still go out (to a
+  // stand-in address and the wave's dump area), which keeps the number of loads per
+  // phase, and with it the vmcnt arithmetic, constant.
+  uint64_t ld_vbase = 0, ld_vbase1 = 0, ld_kbase = 0;
+  uint32_t ld_vdst = 0, ld_kdst = 0, ld_vstep = 0, ld_kstep = 0, ld_klim = 0;   // step: LDS distance of run w + 8
+  // A tile past the end of the schedule is replaced by a stand-in: the first tile of
+  // K / V^T, always readable, loaded into the wave's dump kilobyte.
+  auto load_v_begin = [&](int t, int d) {
+    if (!WITH_V) return;
+    const bool real = t < n_tiles, col = real && is_col(t);
+    const uint32_t off = !real ? 0u : (col ? (uint32_t)t : (uint32_t)first_key(t, d)) * 2u;   // bytes into a V^T row; t * 64 keys for a gathered tile
+    ld_vbase = (col ? s_vct + (uint64_t)((uint32_t)t * (BK * 2u)) : s_vtbase + off);
+    ld_vbase1 = ld_vbase + 128ull * (uint32_t)P.S_pad;            // run w + 8: 64 rows of V^T further on
+    ld_vdst = smem_lds + 1024 * wave + (real ? OFF_V + (t & (NSTAGE - 1)) * VTILE_B : OFF_DUMP);
+    ld_vstep = real ? 8192 : 0;                    // a stand-in tile writes both runs to the same dump kilobyte
   };
-  auto load_k_begin = [&](int t, int d, bool on) {
-    ld_k_on = on;
-    if (ld_k_on) {
-      const Tile T = get_tile(t, d);
-      // a range tile may start past the last key (all of it masked): the base row is
-      // clamped, and so is each lane's byte offset, to the last row that exists
-      const int row0 = min(T.krow0, T.kmax);
-      ld_kbase = scalar_ptr(T.kb + (size_t)row0 * kHeadDim);
-      ld_klim = (uint32_t)(T.kmax - row0) * KROW_B + (koff0 & (KROW_B - 1));
-      ld_kdst = smem_lds + OFF_K + (t & 1) * KTILE_B + 1024 * wave;
-    }
+  auto load_k_begin = [&](int t, int d) {
+    const bool real = t < n_tiles, col = real && is_col(t);
+    const int kmax = col ? P.S_pad - 1 : S - 1;    // last row of the array that may be read
+    // a range tile may start past the last key (all of it masked): the base row is
+    // clamped, and so is each lane's byte offset, to the last row that exists
+    const int row0 = min(!real ? 0 : (col ? t * BK : first_key(t, d)), kmax);
+    ld_kbase = (col ? s_kc : s_kbase) + ((uint64_t)(uint32_t)row0 << 8);
+    ld_klim = (uint32_t)(kmax - row0) * KROW_B + (koff0 & (KROW_B - 1));
+    ld_kdst = smem_lds + 1024 * wave + (real ? OFF_K + (t & (NSTAGE - 1)) * KTILE_B : OFF_DUMP);
+    ld_kstep = real ? 8192 : 0;
   };
   auto load_v_one = [&](int n) {
-    if (ld_v_on) dma16(ld_vbase + (uint64_t)(64 * n) * (uint64_t)P.S_pad, voff0, ld_vdst + 4096 * n);
+    if (!WITH_V) return;
+    dma16(n == 0 ? ld_vbase : ld_vbase1, voff0, __builtin_amdgcn_readfirstlane(ld_vdst + ld_vstep * n));
   };
   auto load_k_one = [&](int n) {
-    if (ld_k_on) dma16(ld_kbase, min(koff0 + 16 * KROW_B * n, ld_klim), ld_kdst + 4096 * n);
+    dma16(ld_kbase, min(koff0 + 32 * KROW_B * n, ld_klim), __builtin_amdgcn_readfirstlane(ld_kdst + ld_kstep * n));
   };
   // the 64 dwords that go with a tile: the key indices of a gathered tile, or for a
-  // range tile 16 words of the offset bitmap (covering every offset of the 128 x 64
-  // tile) followed by the 2 words of the column bitmap.  One load, by wave 0.
+  // range tile 16 words of the offset bitmap (covering every offset of the 256 x 64
+  // tile) followed by the 2 words of the column bitmap.  One load, by wave t % 8.
+  const uint32_t aux_lane = lane < 16 ? 4u * lane : 4u * (lane & 1);
   auto dma_aux = [&](int t, int d) {
-    if (MODE != 2 || wave != 0) return;
-    const Tile T = get_tile(t, d);
-    const uint32_t dst = smem_lds + OFF_A + (t & 3) * AUX_B;
-    if (T.idx != nullptr) {
-      dma4(scalar_ptr(T.idx), 4u * lane, dst);
+    if (MODE != 2 || wave != (t & 7)) return;
+    const bool real = t < n_tiles;
+    const uint32_t dst = smem_lds + (real ? OFF_A + (t & (NAUX - 1)) * AUX_B : OFF_DUMP);
+    if (real && is_col(t)) {
+      dma4(s_cidx + (uint64_t)((uint32_t)t * (BK * 4u)), 4u * lane, dst);
     } else {
-      int wb = (P.off_max - (i0 - T.j0 + BQ - 1)) >> 5;          // first offset-bitmap word needed
+      const int j0 = real ? first_key(t, d) : 0;
+      const int wb = (P.off_max - (i0 - j0 + BQ - 1)) >> 5;          // first offset-bitmap word needed
       // lanes 0..15: offset words wb ..; lanes 16..63: the two column words, alternating.
       // The column bitmaps lie below the offset bitmaps in the workspace (and within
       // 4 GB of them), so offsets from the column word are non-negative 32-bit values.
-      const uint32_t* cw = cbits + (T.j0 >> 5);
-      const uint32_t gap = (uint32_t)((const char*)(obits + wb) - (const char*)cw);
-      dma4(scalar_ptr(cw), lane < 16 ? gap + 4u * lane : 4u * (lane & 1), dst);
+      const uint64_t cw = s_cbits + (uint64_t)((uint32_t)(j0 >> 5) * 4u);
+      const uint32_t gap = (uint32_t)(s_obits + (uint64_t)((uint32_t)wb * 4u) - cw);
+      dma4(cw, aux_lane + (lane < 16 ? gap : 0u), dst);
     }
   };
-  const bool aux_wave = (MODE == 2) && (wave == 0);
 
   // Whether this wave has anything to do on tile t.  For the sparse kernel the answer
-  // needs two of the tile's aux words from LDS; they are read early (act_words) and
+  // needs some of the tile's aux words from LDS; they are read early (act_words) and
   // looked at later (tile_active), so that the wait for them hides behind MFMAs.
-  auto act_words = [&](int t, uint32_t& w0, uint32_t& w1) {
+  //  - gathered tile: its first key index must not lie after the wave's rows;
+  //  - range tile: one of the 95 offsets between the wave's 32 rows and the tile's
+  //    64 keys must be kept (keys after a row give negative offsets, never kept), not
+  //    all 64 keys may be selected columns (the column pass covered those), and the
+  //    tile must start before the sequence end.
+  auto act_words = [&](int t, int d, uint32_t& w0, uint32_t& w1, uint32_t& w2) {
     if (MODE != 2) return;
-    const uint32_t* ax = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & 3) * AUX_B);
-    w0 = ax[t < n_col_tiles ? 0 : 16];             // first key index, or first column-bitmap word
-    w1 = ax[17];                                   // second column-bitmap word (range tiles)
-  };
-  auto tile_active = [&](int t, int d, uint32_t w0, uint32_t w1) -> bool {
-    const Tile T = get_tile(t, d);
-    bool act;
-    if (MODE == 2 && T.kind == TK_COLIDX) {
-      act = (int)w0 <= iw0 + 31;                   // else every column of the tile lies after the wave's rows
+    const uint32_t* ax = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
+    if (t < n_col_tiles) {
+      w0 = ax[0];
     } else {
-      act = T.j0 <= iw0 + 31;                      // else every key of the tile lies after the wave's rows
-      // a range tile whose keys all belong to selected columns was covered by the
-      // column pass; one that starts past the sequence end holds no key at all
-      if (MODE == 2) act = act && ((w0 & w1) != 0xFFFFFFFFu) && (T.j0 < S);
+      const int j0 = first_key(t, d);
+      const int wb = (P.off_max - (i0 - j0 + BQ - 1)) >> 5;
+      const int xs = P.off_max - (iw0 - j0 + 31);          // bit of the largest offset of the window
+      const int kk = (xs >> 5) - wb;                       // 0 .. 7
+      w0 = ax[kk + (lane & 3)];                            // lanes 0..3: the 4 words that hold the 95 bits
+      w1 = ax[16];
+      w2 = ax[17];
+    }
+  };
+  auto tile_active = [&](int t, int d, uint32_t w0, uint32_t w1, uint32_t w2) -> bool {
+    bool act;
+    const int j0 = first_key(t, d);
+    if (is_col(t)) {
+      act = (int)w0 <= iw0 + 31;
+    } else if (MODE == 2) {
+      const int xs = P.off_max - (iw0 - j0 + 31);
+      const int lo = xs & 31;                              // window = bits [lo, lo + 95) of the 4 words
+      const int q = lane & 3;
+      const int b0 = max(lo - 32 * q, 0), b1 = min(lo + 95 - 32 * q, 32);   // bits of word q inside it
+      const uint32_t m = (b1 > b0) ? (uint32_t)(((1ull << (b1 - b0)) - 1ull) << b0) : 0u;
+      const bool hit = (lane < 4) && ((w0 & m) != 0u);
+      act = (__ballot(hit) != 0ull) && ((w1 & w2) != 0xFFFFFFFFu) && (j0 < S);
+    } else {
+      act = j0 <= iw0 + 31;                        // else every key of the tile lies after the wave's rows
     }
     return __builtin_amdgcn_readfirstlane((int)act) != 0;
   };
 
   // ---- operand ring and the MFMA phase -------------------------------------------
-  // A phase issues up to 32 MFMAs: 16 of P V(t) (keys in groups of 16, head-dim
-  // blocks 0..3 within a group) and 16 of K Q^T(t+1) (two 32-key halves, 8
+  // A phase issues up to 32 MFMAs: 16 of P V(t-1) (keys in groups of 16, head-dim
+  // blocks 0..3 within a group) and 16 of K Q^T(t) (two 32-key halves, 8
   // contraction steps each).  Their A operands come from LDS through a ring of 8
   // registers x 16 bytes: after MFMA i has consumed slot i % 8, the operand of MFMA
   // i + 8 is read into it, so every read has 7 MFMAs (~250 cycles) to return and the
@@ -384,16 +369,21 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     const char* vp = smem + OFF_V + buf * VTILE_B + (32 * mb + ql) * VROW_B;
     R[slot] = *reinterpret_cast<const uint4*>(vp + (((4 * sb + 2 * u + hf) ^ ((ql >> 1) & 7)) << 4));
   };
-  // P V(t): on entry the ring holds V operands 0..7 (read during the softmax phase);
-  // the second half of the sweep re-fills it with the first 8 K operands of tile t+1
-  // (read even when that tile turns out to need no work from this wave)
-  auto mm_pv = [&](int bufp, int bufq, auto&& next_tile_setup) {
+  // P V: on entry the ring holds V operands 0..7 (read during the softmax phase);
+  // the second half of the sweep re-fills it with the first 8 K operands of the next
+  // tile (read even when that tile turns out to need no work from this wave).  The
+  // loads of the tiles further ahead go out under the MFMAs: set-up after the first
+  // MFMA has been issued, then one load per 3 MFMAs.
+  auto mm_pv = [&](int bufp, int bufq, auto&& ahead_setup, auto&& look, auto&& decide) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      // the loads of the tile after next go out under the MFMAs: set-up after the
-      // first MFMA has been issued, then one load per 3 MFMAs
-      if (i == 1) next_tile_setup();
-      if (i >= 4 && (i - 4) % 3 == 0) load_k_one((i - 4) / 3);
+      if (i == 1) ahead_setup();
+      if (i == 3) look();                          // read the words that say whether the next tile needs this wave
+      if (i == 4) load_v_one(0);
+      if (i == 7) load_v_one(1);
+      if (i == 9) decide();                        // ... and decide, under the MFMAs
+      if (i == 10) load_k_one(0);
+      if (i == 13) load_k_one(1);
       const int sb = i >> 3, u = (i >> 2) & 1, mb = i & 3;
       uint4 pw = {pk[sb][4 * u], pk[sb][4 * u + 1], pk[sb][4 * u + 2], pk[sb][4 * u + 3]};
       o[mb] = mfma_32x32x16(as_bf16x8(R[i & 7]), as_bf16x8(pw), o[mb]);      // O^T += V^T P^T
@@ -402,17 +392,24 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       SA_PIN();
     }
   };
-  // K Q^T(t+1): the ring holds K operands 0..7 unless `cold`.
-  // Element r of s[sb] is key j0 + 32*sb + 16*(r/8) + 8*hf + r%8 against query i_me.
-  auto mm_qk = [&](int bufq, bool cold) {
-    if (cold) {
+  // first 8 K operands of a tile into the ring (when no P V sweep did it)
+  auto warm_k = [&](int bufq) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ld_k(i, i, bufq);
-    }
+    for (int i = 0; i < 8; ++i) ld_k(i, i, bufq);
     SA_PIN();
+  };
+  // K Q^T: the ring holds K operands 0..7.  `with_loads`: no P V sweep went before,
+  // so this sweep issues the loads of the tiles further ahead.
+  // Element r of s[sb] is key j0 + 32*sb + 16*(r/8) + 8*hf + r%8 against query i_me.
+  auto mm_qk = [&](int bufq, bool with_loads) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      if (cold && (i & 3) == 2) load_k_one(i >> 2);   // not issued by a P V sweep before
+      if (with_loads) {
+        if (i == 2) load_v_one(0);
+        if (i == 5) load_v_one(1);
+        if (i == 8) load_k_one(0);
+        if (i == 11) load_k_one(1);
+      }
       const int sb = i >> 3, ks = i & 7;
       if (ks == 0) {
 #pragma unroll
@@ -427,14 +424,15 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
 
   // ---- the softmax phase: mask, online softmax (one query per lane), bf16 --------
   auto step_softmax = [&](int t, int d) {
-    const Tile T = get_tile(t, d);
-    const int buf = t & 1;
+    const int j0 = first_key(t, d);
+    const int kind = is_col(t) ? TK_COLIDX : (MODE == 2) ? TK_RANGE : (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
+    const int buf = t & (NSTAGE - 1);
     const float ninf = -__builtin_inff();
-    if (T.kind == TK_CAUSAL) {
-      if (T.j0 + BK - 1 > iw0) {
+    if (kind == TK_CAUSAL) {
+      if (j0 + BK - 1 > iw0) {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
-          int tl = i_me - (T.j0 + 32 * sb + 8 * hf);   // keep bit b iff b <= tl
+          int tl = i_me - (j0 + 32 * sb + 8 * hf);   // keep bit b iff b <= tl
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             int b = 16 * (r >> 3) + (r & 7);
@@ -442,8 +440,8 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
           }
         }
       }
-    } else if (MODE == 2 && T.kind == TK_COLIDX) {
-      const int32_t* il = reinterpret_cast<const int32_t*>(smem + OFF_A + (t & 3) * AUX_B);
+    } else if (MODE == 2 && kind == TK_COLIDX) {
+      const int32_t* il = reinterpret_cast<const int32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
       if (il[BK - 1] > iw0) {
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
@@ -457,12 +455,12 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
               s[sb][8 * u + e] = (jj[e] <= i_me) ? s[sb][8 * u + e] : ninf;
           }
       }
-    } else if (MODE == 2 && T.kind == TK_RANGE) {
-      const uint32_t* mw = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & 3) * AUX_B);
-      const int wb = (P.off_max - (i0 - T.j0 + BQ - 1)) >> 5;
+    } else if (MODE == 2 && kind == TK_RANGE) {
+      const uint32_t* mw = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
+      const int wb = (P.off_max - (i0 - j0 + BQ - 1)) >> 5;
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
-        int tl = i_me - (T.j0 + 32 * sb + 8 * hf);
+        int tl = i_me - (j0 + 32 * sb + 8 * hf);
         int x0 = P.off_max - tl;                       // >= 0 by construction of the bitmap
         int k = (x0 >> 5) - wb;                        // 0 .. 8: word of the staged window
         uint32_t lo = mw[k], hi = mw[k + 1];
@@ -517,11 +515,6 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       for (int r = 0; r < 16; ++r) {
         p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_run));
         rs += p[r];
-        if ((r & 7) == 7) {                  // one load of the next V^T tile every 8 keys
-          SA_PIN();
-          load_v_one(2 * sb + (r >> 3));
-          SA_PIN();
-        }
       }
 #pragma unroll
       for (int r = 0; r < 8; ++r) pk[sb][r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
@@ -530,65 +523,78 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   };
 
   // ---- the two-phase pipeline --------------------------------------------------------
-  // Per group and tile t:
-  //   softmax phase(t): issue V(t+1); softmax(t);               wait for K(t+1), aux(t+1)
-  //   MFMA phase(t):    issue aux(t+2), K(t+2); P V(t), K Q^T(t+1);   wait for V(t+1)
-  // The two groups run the same sequence half an iteration apart.  A buffer is
-  // re-filled only after the barrier that follows its last reader; a load is waited
-  // for by the wave that issued it before the barrier that precedes its first reader
-  // (loads complete in order, so "at most n in flight" means everything but the last n
-  // has landed).  The K loads go out between the MFMAs, whose issue slots are mostly
-  // idle, the V loads between the exponentials.
+  // MFMA phase(u):    P V(u-1), K Q^T(u); issue aux(u+3), V(u+2), K(u+3)
+  // softmax phase(u): softmax(u)
+  // Group 0 runs MFMA phase u in global phase 2u, group 1 in 2u + 1.  Slot t % 4 of
+  // the K (V^T) ring is re-filled with tile t + 4 only after the barrier that follows
+  // its last reader - K Q^T(t) (P V(t)) of group 1; a load is waited for by the wave
+  // that issued it before the barrier that precedes its first reader.  Loads complete
+  // in order, so "at most n in flight" means everything but the last n has landed: at
+  // the end of MFMA phase u the loads of phase u - 1 that feed the next softmax and
+  // K Q^T (V(u+1), and K(u+1) from phase u - 2) must be in, the rest may still fly.
   unsigned long long tiles_done = 0;
   bool act_t = false;                        // this wave has work on the tile whose softmax comes next
-  int d0 = fetch_d(0), d1 = fetch_d(1), d2 = 0;   // tile diagonals of tiles t, t+1 and (in flight) t+2
-  auto softmax_phase = [&](int t) {          // window: d0 = tile t, d1 = tile t+1
-    load_v_begin(t + 1, d1, t + 1 < n_tiles);
-    if (act_t) {
-      step_softmax(t, d0);                   // issues the V loads between its exponentials
-    } else {
-#pragma unroll
-      for (int n = 0; n < 4; ++n) load_v_one(n);
+  bool pre_done = false, pre_act = false;    // the next tile was already looked at (and the ring warmed for it)
+  int dq0 = fetch_d(0), dq1 = fetch_d(1), dq2 = fetch_d(2), dq3 = fetch_d(3);   // tile diagonals of tiles u .. u+3
+  auto softmax_phase = [&](int u) {
+    if (act_t) step_softmax(u, dq0);
+    // A wave with nothing to do here looks at the next tile now, so that its next MFMA
+    // phase knows at once whether it has work.
+    if (!act_t && u + 1 < n_tiles) {
+      uint32_t w0 = 0, w1 = 0, w2 = 0;
+      act_words(u + 1, dq1, w0, w1, w2);
+      pre_act = tile_active(u + 1, dq1, w0, w1, w2);
+      pre_done = true;
     }
-    if (ld_v_on) vm_wait<4>(); else vm_wait<0>();
   };
-  auto mfma_phase = [&](int t) {             // window: d0 = tile t+1, d1 = tile t+2; t = -1: only K Q^T(0)
-    const bool have_next = t + 1 < n_tiles;
-    const bool more = t + 2 < n_tiles;
-    uint32_t aw0 = 0, aw1 = 0;
-    if (have_next) act_words(t + 1, aw0, aw1);
-    auto next_tile_setup = [&]() {
-      if (more) dma_aux(t + 2, d1);
-      load_k_begin(t + 2, d1, more);
+  auto mfma_phase = [&](int u) {
+    const bool have = u < n_tiles;
+    auto ahead_setup = [&]() {
+      dma_aux(u + 3, dq3);
+      load_v_begin(u + 2, dq2);
+      load_k_begin(u + 3, dq3);
     };
     __builtin_amdgcn_s_setprio(1);
     const bool pv = WITH_V && act_t;
-    if (pv) mm_pv(t & 1, (t + 1) & 1, next_tile_setup); else next_tile_setup();
-    const bool act_n = have_next && tile_active(t + 1, d0, aw0, aw1);
-    if (act_n) mm_qk((t + 1) & 1, !pv);
+    bool act_n = false;
+    if (pv) {
+      uint32_t aw0 = 0, aw1 = 0, aw2 = 0;
+      auto look = [&]() { if (have) act_words(u, dq0, aw0, aw1, aw2); };
+      auto decide = [&]() { act_n = have && tile_active(u, dq0, aw0, aw1, aw2); };
+      mm_pv((u - 1) & (NSTAGE - 1), u & (NSTAGE - 1), ahead_setup, look, decide);
+    } else {
+      ahead_setup();
+      if (pre_done) {
+        act_n = pre_act;
+        if (act_n) warm_k(u & (NSTAGE - 1));
+      } else if (have) {
+        uint32_t aw0 = 0, aw1 = 0, aw2 = 0;
+        act_words(u, dq0, aw0, aw1, aw2);
+        act_n = tile_active(u, dq0, aw0, aw1, aw2);
+        if (act_n) warm_k(u & (NSTAGE - 1));
+      }
+    }
+    pre_done = false;
+    if (act_n) mm_qk(u & (NSTAGE - 1), !pv);
     __builtin_amdgcn_s_setprio(0);
     if (!pv && !act_n) {
-#pragma unroll
-      for (int n = 0; n < 4; ++n) load_k_one(n);
+      load_v_one(0); load_v_one(1); load_k_one(0); load_k_one(1);
     }
     tiles_done += act_n ? 1 : 0;
     act_t = act_n;
-    if (WITH_V) {                            // V(t+1) went out before the loads of this phase
-      if (!more) vm_wait<0>();
-      else if (aux_wave) vm_wait<5>();
-      else vm_wait<4>();
-    }
+    // everything but this phase's loads and the K loads of the one before has landed
+    // (the wave that also fetched aux words waits for one load more than it must)
+    if (WITH_V) vm_wait<6>(); else vm_wait<4>();
   };
 #undef SA_PIN
 
-  // prologue: K(0), V(0) and the aux words of tile 0
-  if (n_tiles > 0) {
-    dma_aux(0, d0);
-    load_k_begin(0, d0, true);
-    load_v_begin(0, d0, true);
-#pragma unroll
-    for (int n = 0; n < 4; ++n) { load_k_one(n); load_v_one(n); }
-  }
+  // prologue: K(0..2), V(0..1) and the aux words of tiles 0..2
+  dma_aux(0, dq0); dma_aux(1, dq1); dma_aux(2, dq2);
+  load_k_begin(0, dq0); load_k_one(0); load_k_one(1);
+  load_k_begin(1, dq1); load_k_one(0); load_k_one(1);
+  load_k_begin(2, dq2); load_k_one(0); load_k_one(1);
+  load_v_begin(0, dq0); load_v_one(0); load_v_one(1);
+  load_v_begin(1, dq1); load_v_one(0); load_v_one(1);
   // vmcnt(0), as the builtin: the compiler then also knows that the Q loads above have
   // landed and places no waits of its own for them inside the loop, where they would
   // wait for the loads in flight there as well
@@ -597,15 +603,16 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   // group 1 starts one barrier late and group 0 passes one more at the end, so the
   // MFMA phase of one group always coincides with the softmax phase of the other
   if (grp == 1) wg_barrier();
-  for (int t = 0; t < n_iter; ++t) {
-    mfma_phase(t - 1);                       // t = 0: K Q^T(0) only
+  for (int u = 0; u < n_tiles; ++u) {
+    mfma_phase(u);                           // u = 0: K Q^T(0) only
     wg_barrier();
-    d2 = fetch_d(t + 2);                     // in flight during the softmax phase
-    softmax_phase(t);
+    const int dq4 = fetch_d(u + 4);          // in flight during the softmax phase
+    softmax_phase(u);
     wg_barrier();
-    d0 = d1; d1 = d2;
+    dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
   }
-  mfma_phase(n_iter - 1);                    // the last P V
+  mfma_phase(n_tiles);                       // the last P V
+  vm_wait<0>();                              // nothing may still be writing LDS when the workgroup ends
   if (grp == 0) wg_barrier();
 
   // ---- epilogue -------------------------------------------------------------
@@ -639,7 +646,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
 
 template <int MODE, bool OUT_F32>
 static hipError_t launch_one(const FlashParams& P, int grid, hipStream_t st) {
-  size_t shmem = 2 * GROUP_B;
+  size_t shmem = LDS_B;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kernel<MODE, OUT_F32>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return e;
@@ -649,11 +656,10 @@ static hipError_t launch_one(const FlashParams& P, int grid, hipStream_t st) {
 
 hipError_t launch_flash(int mode, bool out_f32, const FlashParams& P, hipStream_t st) {
   int grid;
-  const int n_pairs = (P.n_qtiles + 1) / 2;
   if (mode == 2) {
-    grid = (P.n_bh >= 8) ? 8 * n_pairs * ((P.n_bh + 7) / 8) : n_pairs * P.n_bh;
+    grid = (P.n_bh >= 8) ? 8 * P.n_qtiles * ((P.n_bh + 7) / 8) : P.n_qtiles * P.n_bh;
   } else {
-    int bundles = n_pairs * P.n_bkv;
+    int bundles = P.n_qtiles * P.n_bkv;
     grid = ((bundles + 7) / 8) * 8 * P.group;
   }
   if (grid <= 0) return hipSuccess;

@@ -105,16 +105,16 @@ __device__ bool any_offset(const uint32_t* ob, int off_max, int lo, int hi) {
   return false;
 }
 
-// Tile diagonal d pairs the 128-row query tile starting at row i0 with the
-// 64-key tile starting at key i0 + 64 - 64 d: it spans offsets
-// [64 d - 127, 64 d + 63].  dlist = ascending d with at least one kept offset.
+// Tile diagonal d pairs the 256-row query tile starting at row i0 with the
+// 64-key tile starting at key i0 + 192 - 64 d: it spans offsets
+// [64 d - 255, 64 d + 63].  dlist = ascending d with at least one kept offset.
 __global__ __launch_bounds__(256) void dlist_kernel(MaskPrepParams P) {
   __shared__ int wave_cnt[4];
   __shared__ int base;
   const int h = blockIdx.x;
   const uint32_t* ob = P.off_bits + (size_t)h * P.rb_words;
   int32_t* dl = P.dlist + (size_t)h * P.dlist_stride;
-  const int nd = (P.S + 63) / 64 + 1;
+  const int nd = (P.S + 63) / 64 + 3;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid == 0) base = 0;
   __syncthreads();
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void dlist_kernel(MaskPrepParams P) {
     int d = d0 + tid;
     bool f = false;
     if (d < nd) {
-      int lo = max(0, 64 * d - 127), hi = min(P.S - 1, 64 * d + 63);
+      int lo = max(0, 64 * d - 255), hi = min(P.S - 1, 64 * d + 63);
       f = (lo <= hi) && any_offset(ob, P.off_max, lo, hi);
     }
     unsigned long long b = __ballot(f);

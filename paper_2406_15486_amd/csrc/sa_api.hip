@@ -27,7 +27,7 @@ sa_status check_shape(const sa_shape* s, Dims* d) {
   if ((long long)s->batch * s->n_q_heads > 65535) return SA_ERR_UNSUPPORTED;
   if (s->seq_len > (1 << 24)) return SA_ERR_UNSUPPORTED;   // kernels keep 32-bit byte offsets into V^T
   d->S = s->seq_len;
-  d->S_pad = (s->seq_len + 127) / 128 * 128;
+  d->S_pad = (s->seq_len + sa::kFlashBQ - 1) / sa::kFlashBQ * sa::kFlashBQ;
   d->n_bh = s->batch * s->n_q_heads;
   d->n_bkv = s->batch * s->n_kv_heads;
   d->group = s->n_q_heads / s->n_kv_heads;
@@ -69,8 +69,8 @@ struct SparseWs {
 SparseWs sparse_ws(const Dims& d) {
   SparseWs w;
   w.cb_words = d.S_pad / 32 + 2;
-  w.rb_words = d.S_pad / 32 + 8;
-  w.dlist_stride = d.S_pad / 64 + 2;
+  w.rb_words = d.S_pad / 32 + 24;
+  w.dlist_stride = d.S_pad / 64 + 8;
   w.off_max = d.S_pad - 1;
   size_t at = 0;
   w.vt = at;    at += align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2);

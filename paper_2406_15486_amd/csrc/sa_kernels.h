@@ -6,7 +6,7 @@
 namespace sa {
 
 constexpr int kHeadDim = 128;  // the only supported head dimension
-constexpr int kFlashBQ = 128;  // query rows per workgroup of the flash kernels
+constexpr int kFlashBQ = 256;  // query rows per workgroup of the flash kernels
 constexpr int kFlashBK = 64;   // keys per tile
 
 struct FlashParams {
@@ -18,7 +18,7 @@ struct FlashParams {
   int S, S_pad;
   int n_bh, n_bkv, group;   // batch*q-heads, batch*kv-heads, q heads per kv head
   float scale_log2;         // softmax scale * log2(e)
-  int n_qtiles;             // 128-row query tiles to process
+  int n_qtiles;             // 256-row query tiles to process
   int q_row0, n_qrows;      // first query row and number of rows (sampled rows in mode 1)
   // strip-masked mode only
   const uint16_t* kc;           // [n_bh, S_pad, 128] K rows gathered by column index
