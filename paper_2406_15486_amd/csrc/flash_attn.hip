@@ -345,8 +345,8 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
 
   // ---- operand ring and the MFMA phase -------------------------------------------
   // A phase issues up to 32 MFMAs: 16 of P V(t-1) (keys in groups of 16, head-dim
-  // blocks 0..3 within a group) and 16 of K Q^T(t) (two 32-key halves, 8
-  // contraction steps each).  Their A operands come from LDS through a ring of 8
+  // blocks 0..3 within a group) and 16 of K Q^T(t) (8 contraction steps for each
+  // of two 32-key halves).  Their A operands come from LDS through a ring of 8
   // registers x 16 bytes: after MFMA i has consumed slot i % 8, the operand of MFMA
   // i + 8 is read into it, so every read has 7 MFMAs (~250 cycles) to return and the
   // matrix pipe does not wait on LDS round trips.  sched_barrier pins the order: the
@@ -355,10 +355,11 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   uint32_t pk[2][8];
   uint4 R[8];
 #define SA_PIN() __builtin_amdgcn_sched_barrier(0)
-  // K operand i = 8 sb + ks: 32-key half sb, contraction step ks
+  // K operand i = 2 ks + sb: contraction step ks, 32-key half sb (the halves alternate
+  // so that consecutive MFMAs of the sweep accumulate into different registers)
   auto ld_k = [&](int slot, int i, int buf) {
     // row p = 32 sb + ql; logical chunk 2 ks + hf lives at physical chunk (2 ks + hf) ^ (p & 15)
-    const int sb = i >> 3, ks = i & 7;
+    const int sb = i & 1, ks = i >> 1;
     const char* kp = smem + OFF_K + buf * KTILE_B + (32 * sb + ql) * KROW_B;
     R[slot] = *reinterpret_cast<const uint4*>(kp + (((2 * ks + hf) ^ (ql & 15)) << 4));
   };
@@ -410,7 +411,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
         if (i == 8) load_k_one(0);
         if (i == 11) load_k_one(1);
       }
-      const int sb = i >> 3, ks = i & 7;
+      const int sb = i & 1, ks = i >> 1;
       if (ks == 0) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
