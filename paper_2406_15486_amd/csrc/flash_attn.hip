@@ -537,7 +537,20 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   bool act_t = false;                        // this wave has work on the tile whose softmax comes next
   bool pre_done = false, pre_act = false;    // the next tile was already looked at (and the ring warmed for it)
   int dq0 = fetch_d(0), dq1 = fetch_d(1), dq2 = fetch_d(2), dq3 = fetch_d(3);   // tile diagonals of tiles u .. u+3
+  // The scores, the probabilities and the operand ring are written on some paths only
+  // (a wave may have no work on a tile).  An empty asm that "defines" them where their
+  // old contents are dead tells the compiler so; without it every path that skips a
+  // write carries the old value along, and the register allocator copies whole arrays
+  // between two homes inside the loop.
+  auto forget_ring_and_p = [&]() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) asm volatile("" : "=v"(R[i]));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) asm volatile("" : "=v"(pk[0][i]), "=v"(pk[1][i]));
+  };
+  auto forget_scores = [&]() { asm volatile("" : "=v"(s[0]), "=v"(s[1])); };
   auto softmax_phase = [&](int u) {
+    forget_ring_and_p();                     // consumed by the MFMA phase before
     if (act_t) step_softmax(u, dq0);
     // A wave with nothing to do here looks at the next tile now, so that its next MFMA
     // phase knows at once whether it has work.
@@ -549,6 +562,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     }
   };
   auto mfma_phase = [&](int u) {
+    forget_scores();                         // consumed by the softmax phase before
     const bool have = u < n_tiles;
     auto ahead_setup = [&]() {
       dma_aux(u + 3, dq3);
