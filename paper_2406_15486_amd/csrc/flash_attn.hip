@@ -428,54 +428,63 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     const int j0 = first_key(t, d);
     const int kind = is_col(t) ? TK_COLIDX : (MODE == 2) ? TK_RANGE : (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
     const int buf = t & (NSTAGE - 1);
-    const float ninf = -__builtin_inff();
+    // Mask: one 32-bit pattern per lane and 32-key half, bit b <-> key
+    // j0 + 32 sb + 8 hf + b of the lane's 16 (b = 0..7, 16..23), set = keep.  The
+    // pattern is built per tile kind; one loop applies it (a 1-bit signed extract and
+    // a bitwise select between the score and -inf per element).
+    bool masked = false;                   // wave-uniform
+    uint32_t km[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};
     if (kind == TK_CAUSAL) {
-      if (j0 + BK - 1 > iw0) {
+      if (j0 + BK - 1 > iw0) {             // keep key <= query, i.e. b <= tl
+        masked = true;
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
-          int tl = i_me - (j0 + 32 * sb + 8 * hf);   // keep bit b iff b <= tl
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            int b = 16 * (r >> 3) + (r & 7);
-            s[sb][r] = (b <= tl) ? s[sb][r] : ninf;
-          }
+          const int tl = i_me - (j0 + 32 * sb + 8 * hf);
+          km[sb] = tl < 0 ? 0u : (tl >= 31 ? 0xFFFFFFFFu : (2u << tl) - 1u);
         }
       }
     } else if (MODE == 2 && kind == TK_COLIDX) {
       const int32_t* il = reinterpret_cast<const int32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
-      if (il[BK - 1] > iw0) {
+      if (il[BK - 1] > iw0) {              // only the last gathered tiles reach past a row: keep index <= query
+        masked = true;
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
+        for (int sb = 0; sb < 2; ++sb) {
+          uint32_t m = 0;
 #pragma unroll
           for (int u = 0; u < 2; ++u) {
             const int4* ip = reinterpret_cast<const int4*>(il + 32 * sb + 16 * u + 8 * hf);
             int4 x0 = ip[0], x1 = ip[1];
             int jj[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-              s[sb][8 * u + e] = (jj[e] <= i_me) ? s[sb][8 * u + e] : ninf;
+            for (int e = 0; e < 8; ++e) m |= (jj[e] <= i_me ? 1u : 0u) << (16 * u + e);
           }
+          km[sb] = m;
+        }
       }
     } else if (MODE == 2 && kind == TK_RANGE) {
+      masked = true;
       const uint32_t* mw = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
       const int wb = (P.off_max - (i0 - j0 + BQ - 1)) >> 5;
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
         int tl = i_me - (j0 + 32 * sb + 8 * hf);
         int x0 = P.off_max - tl;                       // >= 0 by construction of the bitmap
-        int k = (x0 >> 5) - wb;                        // 0 .. 8: word of the staged window
+        int k = (x0 >> 5) - wb;                        // 0 .. 10: word of the staged window
         uint32_t lo = mw[k], hi = mw[k + 1];
         uint32_t ow = __builtin_amdgcn_alignbit(hi, lo, x0 & 31);  // bit b <-> offset tl - b
         uint32_t cw = mw[16 + sb] >> (8 * hf);                     // bit 16u+e <-> key is a selected column
-        uint32_t km = ow & ~cw;
+        km[sb] = ow & ~cw;
+      }
+    }
+    if (masked) {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          int b = 16 * (r >> 3) + (r & 7);
-          // all-ones where the pair is kept; then a bitwise select between score and -inf
-          uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(km, b, 1);
+          const int bit = 16 * (r >> 3) + (r & 7);
+          const uint32_t keep = (uint32_t)__builtin_amdgcn_sbfe(km[sb], bit, 1);   // all-ones where kept
           s[sb][r] = __uint_as_float((__float_as_uint(s[sb][r]) & keep) | (0xFF800000u & ~keep));
         }
-      }
     }
 
     float mx = s[0][0];
