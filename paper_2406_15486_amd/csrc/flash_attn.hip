@@ -535,10 +535,10 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   // ---- the two-phase pipeline --------------------------------------------------------
   // MFMA phase(u):    P V(u-1), K Q^T(u); issue aux(u+3), V(u+2), K(u+3)
   // softmax phase(u): softmax(u)
-  // Group 0 runs MFMA phase u in global phase 2u, group 1 in 2u + 1.  Slot t % 4 of
-  // the K (V^T) ring is re-filled with tile t + 4 only after the barrier that follows
-  // its last reader - K Q^T(t) (P V(t)) of group 1; a load is waited for by the wave
-  // that issued it before the barrier that precedes its first reader.  Loads complete
+  // Group 0 runs MFMA phase u in the first half of iteration u, group 1 in the second.
+  // Slot t % 4 of the K (V^T) ring is re-filled with tile t + 4 only after the barrier
+  // that follows its last reader - K Q^T(t) (P V(t)) of group 1; a load is waited for
+  // by the wave that issued it before the barrier that precedes its first reader.  Loads complete
   // in order, so "at most n in flight" means everything but the last n has landed: at
   // the end of MFMA phase u the loads of phase u - 1 that feed the next softmax and
   // K Q^T (V(u+1), and K(u+1) from phase u - 2) must be in, the rest may still fly.
@@ -558,15 +558,15 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     for (int i = 0; i < 8; ++i) asm volatile("" : "=v"(pk[0][i]), "=v"(pk[1][i]));
   };
   auto forget_scores = [&]() { asm volatile("" : "=v"(s[0]), "=v"(s[1])); };
-  auto softmax_phase = [&](int u) {
+  auto softmax_phase = [&](int u, int d_u, int d_next) {   // tile diagonals of tiles u and u + 1
     forget_ring_and_p();                     // consumed by the MFMA phase before
-    if (act_t) step_softmax(u, dq0);
+    if (act_t) step_softmax(u, d_u);
     // A wave with nothing to do here looks at the next tile now, so that its next MFMA
     // phase knows at once whether it has work.
     if (!act_t && u + 1 < n_tiles) {
       uint32_t w0 = 0, w1 = 0, w2 = 0;
-      act_words(u + 1, dq1, w0, w1, w2);
-      pre_act = tile_active(u + 1, dq1, w0, w1, w2);
+      act_words(u + 1, d_next, w0, w1, w2);
+      pre_act = tile_active(u + 1, d_next, w0, w1, w2);
       pre_done = true;
     }
   };
@@ -624,20 +624,33 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   // wait for the loads in flight there as well
   __builtin_amdgcn_s_waitcnt(0x0f70);
   wg_barrier();
-  // group 1 starts one barrier late and group 0 passes one more at the end, so the
-  // MFMA phase of one group always coincides with the softmax phase of the other
-  if (grp == 1) wg_barrier();
-  for (int u = 0; u < n_tiles; ++u) {
-    mfma_phase(u);                           // u = 0: K Q^T(0) only
-    wg_barrier();
-    const int dq4 = fetch_d(u + 4);          // in flight during the softmax phase
-    softmax_phase(u);
-    wg_barrier();
-    dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
+  // Iteration n: group 0 runs MFMA phase n, then softmax phase n; group 1 runs softmax
+  // phase n - 1, then MFMA phase n; one workgroup barrier ends the iteration.  The
+  // barrier is all the LDS traffic needs (a stage is re-filled, and a landed tile is
+  // first read, at least one iteration after the other side touched it - see above);
+  // starting the two groups on opposite phases after each barrier is what keeps one
+  // wave of every SIMD on the matrix pipe while the other is on the vector pipe.
+  // (The loop is written out once per group: one loop that picks the phase at run
+  // time keeps the registers of both phases alive everywhere and spills.)
+  if (grp == 0) {
+    for (int n = 0; n <= n_tiles; ++n) {
+      mfma_phase(n);                         // n = 0: K Q^T(0) only; n = n_tiles: the last P V
+      softmax_phase(n, dq0, dq1);
+      wg_barrier();
+      const int dq4 = fetch_d(n + 4);        // in flight during the next iteration
+      dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
+    }
+  } else {
+    int dprev = 0;                           // tile diagonal of tile n - 1
+    for (int n = 0; n <= n_tiles; ++n) {
+      softmax_phase(n - 1, dprev, dq0);
+      mfma_phase(n);
+      wg_barrier();
+      const int dq4 = fetch_d(n + 4);
+      dprev = dq0; dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
+    }
   }
-  mfma_phase(n_tiles);                       // the last P V
   vm_wait<0>();                              // nothing may still be writing LDS when the workgroup ends
-  if (grp == 0) wg_barrier();
 
   // ---- epilogue -------------------------------------------------------------
   float l_tot = half_sum(l_run);
