@@ -373,14 +373,16 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   // P V: on entry the ring holds V operands 0..7 (read during the softmax phase);
   // the second half of the sweep re-fills it with the first 8 K operands of the next
   // tile (read even when that tile turns out to need no work from this wave).  The
-  // loads of the tiles further ahead go out under the MFMAs: set-up after the first
-  // MFMA has been issued, then one load per 3 MFMAs.
-  auto mm_pv = [&](int bufp, int bufq, auto&& ahead_setup, auto&& look, auto&& decide) {
+  // loads of the tiles further ahead go out under the MFMAs, one per 3 MFMAs.
+  auto mm_pv = [&](int bufp, int bufq, auto&& setup_a, auto&& setup_v, auto&& setup_k, auto&& look, auto&& decide) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      if (i == 1) ahead_setup();
+      // scalar bookkeeping in small pieces, so that no gap between two MFMAs grows long
+      if (i == 1) setup_a();
+      if (i == 2) setup_v();
       if (i == 3) look();                          // read the words that say whether the next tile needs this wave
       if (i == 4) load_v_one(0);
+      if (i == 5) setup_k();
       if (i == 7) load_v_one(1);
       if (i == 9) decide();                        // ... and decide, under the MFMAs
       if (i == 10) load_k_one(0);
@@ -573,11 +575,10 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   auto mfma_phase = [&](int u) {
     forget_scores();                         // consumed by the softmax phase before
     const bool have = u < n_tiles;
-    auto ahead_setup = [&]() {
-      dma_aux(u + 3, dq3);
-      load_v_begin(u + 2, dq2);
-      load_k_begin(u + 3, dq3);
-    };
+    auto setup_a = [&]() { dma_aux(u + 3, dq3); };
+    auto setup_v = [&]() { load_v_begin(u + 2, dq2); };
+    auto setup_k = [&]() { load_k_begin(u + 3, dq3); };
+    auto ahead_setup = [&]() { setup_a(); setup_v(); setup_k(); };
     __builtin_amdgcn_s_setprio(1);
     const bool pv = WITH_V && act_t;
     bool act_n = false;
@@ -585,7 +586,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       uint32_t aw0 = 0, aw1 = 0, aw2 = 0;
       auto look = [&]() { if (have) act_words(u, dq0, aw0, aw1, aw2); };
       auto decide = [&]() { act_n = have && tile_active(u, dq0, aw0, aw1, aw2); };
-      mm_pv((u - 1) & (NSTAGE - 1), u & (NSTAGE - 1), ahead_setup, look, decide);
+      mm_pv((u - 1) & (NSTAGE - 1), u & (NSTAGE - 1), setup_a, setup_v, setup_k, look, decide);
     } else {
       ahead_setup();
       if (pre_done) {
