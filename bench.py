@@ -59,6 +59,28 @@ def mask_density(S: int, cols: np.ndarray, offs: np.ndarray, window: int) -> flo
     return (n_col + n_off - both) / (S * (S + 1) / 2.0)
 
 
+def touched_block_fraction(S: int, cols: np.ndarray, offs: np.ndarray, window: int, blk: int = 128) -> float:
+    """Fraction of the blk x blk blocks of the causal triangle that hold at least one kept
+    (query, key) pair for one head - the paper's "ratio of calculated blocks" grid (counting only)."""
+    nb = (S + blk - 1) // blk
+    col_blk = np.zeros(nb, dtype=bool)
+    col_blk[np.unique(cols.astype(np.int64) // blk)] = True
+    off_keep = np.zeros(S, dtype=bool)
+    off_keep[offs] = True
+    off_keep[:window] = True
+    oo = np.nonzero(off_keep)[0].astype(np.int64)
+    touched = 0
+    for bi in range(nb):
+        row = col_blk[:bi + 1].copy()                # a kept column j touches every block row >= j // blk
+        lo = np.maximum(bi * blk, oo)                # rows of this block row that have a key at offset o
+        hi = min((bi + 1) * blk, S) - 1
+        ok = lo <= hi
+        row[(lo[ok] - oo[ok]) // blk] = True
+        row[(hi - oo[ok]) // blk] = True
+        touched += int(row.sum())
+    return touched / (nb * (nb + 1) / 2.0)
+
+
 def cpu_baseline(wl, x, alpha: float, budget_s: float) -> dict:
     """Oracle timing on a bounded sample (about 2 x budget_s of CPU work), scaled
     linearly to ms per layer.  The oracle runs as it stands: numpy fp64 on the
@@ -185,6 +207,16 @@ def main() -> int:
     ci = plan.col_idx[0, :int(cc[0])].cpu().numpy()
     si = plan.slash_idx[0, :int(sc[0])].cpu().numpy()
     density0 = mask_density(S, ci, si, w)
+    blocks0 = touched_block_fraction(S, ci, si, w)
+    # stages 1-2 against HBM: algorithmic bytes (K once per KV head and pass, the sampled Q rows,
+    # the row statistics, the two score vectors; five passes over the scores for the selection)
+    kv_b, qr_b, lse_b, sc_b = Hkv * S * 128 * 2, Hq * n_s * 128 * 2, Hq * n_s * 4, 2 * Hq * S * 4
+    stage_bytes = {
+        "row_lse": kv_b + qr_b + lse_b,
+        "score_accum": kv_b + qr_b + lse_b + sc_b,
+        "select": 5 * sc_b + 4 * float(cc.sum() + sc.sum()),
+    }
+    stage_gbs = {n: stage_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in stage_bytes if stage_ms.get(n)}
 
     # ---- in-library dense kernel on the same inputs --------------------------------
     dense_ms = None
@@ -276,6 +308,8 @@ def main() -> int:
         "stage_ms": stage_ms,
         "computed_tile_fraction": float(tiles.sum()) / dense_tiles,
         "mask_density_head0": density0,
+        "touched_128x128_block_fraction_head0": blocks0,
+        "stage_hbm_gbs_algorithmic": stage_gbs,
         "mean_k_c": float(cc.mean()), "mean_k_s": float(sc.mean()),
         "dense_ms": dense_ms,
         "dense_kernel_tflops": dense_kernel_tflops if dense_ms else None,
