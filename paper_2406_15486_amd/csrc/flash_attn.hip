@@ -47,7 +47,7 @@ constexpr int OFF_V = OFF_K + NSTAGE * KTILE_B;
 constexpr int OFF_A = OFF_V + NSTAGE * VTILE_B;
 constexpr int OFF_DUMP = OFF_A + NAUX * AUX_B;      // 1 KB per wave: where loads of tiles past the end go
 constexpr int LDS_B = OFF_DUMP + 8 * 1024;          // 141312 bytes
-constexpr float kLazy = 8.0f;         // rescale only when a row maximum grows by more than 2^8
+constexpr float kSumBound = 256.0f;    // a tile's exponentials may sum to 2^8 per lane before the reference maximum moves
 
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
 
@@ -489,28 +489,6 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
         }
     }
 
-    float mx = s[0][0];
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
-    mx = half_max(mx);
-    // lazy rescale: keep the old reference maximum unless it grew by more than
-    // 2^kLazy (probabilities then stay <= 2^kLazy, exact in fp32 and bf16 alike)
-    const float m_cand = mx * c2;
-    const bool grow = m_cand > m_run + kLazy;
-    if (__any(grow)) {
-      float m_new = grow ? m_cand : m_run;
-      float alpha = fast_exp2(m_run - m_new);
-      m_run = m_new;
-      l_run *= alpha;
-      if (WITH_V) {
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
-      }
-    }
     // the operand ring is idle: fetch the first 8 V operands of this tile's P V now,
     // so that the reads return under the exponentials
     if (WITH_V) {
@@ -519,17 +497,48 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       for (int i = 0; i < 8; ++i) ld_v(i, i, buf);
       SA_PIN();
     }
+    // Online softmax, optimistic: the exponentials are taken against the reference
+    // maximum the row already has, and only their sum is looked at.  A sum within
+    // 2^8 means that no probability exceeds 2^8, which is all the reference is
+    // for (exact in fp32 and bf16 alike); then the tile costs no maximum at all.
+    // Otherwise (first tiles of a row, or a score far above what the row has seen: the
+    // sum is large, inf or NaN) the row maximum of the tile is formed, the reference
+    // moved up to it, the accumulators rescaled and the exponentials taken again.
     float rs = 0.f;
+    auto exponentials = [&]() {
+      rs = 0.f;
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      float p[16];
+      for (int sb = 0; sb < 2; ++sb) {
+        float p[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_run));
-        rs += p[r];
+        for (int r = 0; r < 16; ++r) {
+          p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_run));
+          rs += p[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) pk[sb][r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
       }
+    };
+    exponentials();
+    if (__any(!(rs <= kSumBound))) {
+      float mx = s[0][0];
 #pragma unroll
-      for (int r = 0; r < 8; ++r) pk[sb][r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+      mx = half_max(mx);                     // the two lanes of a row agree on its reference
+      const float m_cand = mx * c2;
+      const float m_new = (m_cand > m_run) ? m_cand : m_run;
+      const float alpha = fast_exp2(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+      if (WITH_V) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
+      }
+      exponentials();
     }
     l_run += rs;
   };
