@@ -35,6 +35,7 @@ constexpr int BK = kFlashBK;          // 64 keys per tile
 constexpr int NT = 512;               // two groups of four waves
 constexpr int NSTAGE = 4;             // K and V^T tiles resident in LDS
 constexpr int NAUX = 8;               // ring of aux-word slots
+constexpr int kDiagMask = 0x00FFFFFF;  // a tile-diagonal list entry: diagonal in bits 0..23, one bit per wave above
 // LDS tiles are unpadded (the direct global->LDS loads write 1 KB runs); bank
 // conflicts are avoided by XOR-swizzling the 16-byte chunk index with the row.
 constexpr int KROW_B = 256;           // bytes per K row in LDS: 16 chunks, chunk c of row p stored at c ^ (p & 15)
@@ -51,13 +52,15 @@ constexpr float kSumBound = 256.0f;    // a tile's exponentials may sum to 2^8 p
 
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
 
-// a wave-uniform pointer, forced into scalar registers
-__device__ __forceinline__ uint64_t scalar_ptr(const void* p) {
-  const uint64_t v = reinterpret_cast<uint64_t>(p);
+// a wave-uniform 64-bit value / pointer, forced into scalar registers (the inline
+// assembly below takes its base address in a scalar register pair; left alone, the
+// compiler may do wave-uniform address arithmetic in vector registers)
+__device__ __forceinline__ uint64_t scalar_u64(uint64_t v) {
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
   return ((uint64_t)hi << 32) | lo;
 }
+__device__ __forceinline__ uint64_t scalar_ptr(const void* p) { return scalar_u64(reinterpret_cast<uint64_t>(p)); }
 // Direct global -> LDS load: lane l of the wave moves N bytes from global address
 // `base` + `off` (base wave-uniform, in scalar registers; off per lane) to LDS
 // address `lds` + N * l (`lds` wave-uniform, passed in M0).  It is written as inline
@@ -65,12 +68,18 @@ __device__ __forceinline__ uint64_t scalar_ptr(const void* p) {
 // compiler, when it issues this instruction itself, makes every later LDS read wait
 // for all of them (it cannot tell the buffers apart), which serialises the prefetch
 // with the arithmetic.  The loads of a wave complete in order.
+// The wave-uniform operands are forced into scalar registers here, whatever the
+// compiler made of the address arithmetic (free when they already are scalar).
 __device__ __forceinline__ void dma16(uint64_t base, uint32_t off, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds)
+  const uint64_t sbase = scalar_u64(base);
+  const uint32_t slds = __builtin_amdgcn_readfirstlane(lds);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(sbase), "s"(slds)
                : "memory", "m0");
 }
 __device__ __forceinline__ void dma4(uint64_t base, uint32_t off, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds)
+  const uint64_t sbase = scalar_u64(base);
+  const uint32_t slds = __builtin_amdgcn_readfirstlane(lds);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(sbase), "s"(slds)
                : "memory", "m0");
 }
 // wait until at most N of this wave's vector-memory loads are still in flight
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     lo = 0; hi = dc;               // tile diagonals d whose key tile a64 + 3 - d is >= 0
     while (lo < hi) {
       int mid = (lo + hi) >> 1;
-      if (dl[mid] <= a64 + 3) lo = mid + 1; else hi = mid;
+      if ((dl[mid] & kDiagMask) <= a64 + 3) lo = mid + 1; else hi = mid;
     }
     n_rng = lo;
     cbits = P.col_bits + (size_t)bh * P.cb_words;
@@ -197,8 +206,8 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   };
   // kind and first key of tile t (wave-uniform; no memory access)
   auto is_col = [&](int t) -> bool { return MODE == 2 && t < n_col_tiles; };
-  auto first_key = [&](int t, int d) -> int {          // contiguous tiles only
-    return (MODE == 2) ? (a64 + 3 - d) * BK : t * BK;
+  auto first_key = [&](int t, int d) -> int {          // contiguous tiles only; d = list entry
+    return (MODE == 2) ? (a64 + 3 - (d & kDiagMask)) * BK : t * BK;
   };
   // array bases as scalars, once
   const uint64_t s_kbase = scalar_ptr(kbase), s_vtbase = scalar_ptr(vtbase);
@@ -256,7 +265,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     if (!WITH_V) return;
     const bool real = t < n_tiles, col = real && is_col(t);
     const uint32_t off = !real ? 0u : (col ? (uint32_t)t : (uint32_t)first_key(t, d)) * 2u;   // bytes into a V^T row; t * 64 keys for a gathered tile
-    ld_vbase = (col ? s_vct + (uint64_t)((uint32_t)t * (BK * 2u)) : s_vtbase + off);
+    ld_vbase = col ? s_vct + (uint64_t)((uint32_t)t * (BK * 2u)) : s_vtbase + off;
     ld_vbase1 = ld_vbase + 128ull * (uint32_t)P.S_pad;            // run w + 8: 64 rows of V^T further on
     ld_vdst = smem_lds + 1024 * wave + (real ? OFF_V + (t & (NSTAGE - 1)) * VTILE_B : OFF_DUMP);
     ld_vstep = real ? 8192 : 0;                    // a stand-in tile writes both runs to the same dump kilobyte
@@ -274,10 +283,10 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   };
   auto load_v_one = [&](int n) {
     if (!WITH_V) return;
-    dma16(n == 0 ? ld_vbase : ld_vbase1, voff0, __builtin_amdgcn_readfirstlane(ld_vdst + ld_vstep * n));
+    dma16(n == 0 ? ld_vbase : ld_vbase1, voff0, ld_vdst + ld_vstep * n);
   };
   auto load_k_one = [&](int n) {
-    dma16(ld_kbase, min(koff0 + 32 * KROW_B * n, ld_klim), __builtin_amdgcn_readfirstlane(ld_kdst + ld_kstep * n));
+    dma16(ld_kbase, min(koff0 + 32 * KROW_B * n, ld_klim), ld_kdst + ld_kstep * n);
   };
   // the 64 dwords that go with a tile: the key indices of a gathered tile, or for a
   // range tile 16 words of the offset bitmap (covering every offset of the 256 x 64
@@ -301,42 +310,33 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     }
   };
 
-  // Whether this wave has anything to do on tile t.  For the sparse kernel the answer
-  // needs some of the tile's aux words from LDS; they are read early (act_words) and
-  // looked at later (tile_active), so that the wait for them hides behind MFMAs.
-  //  - gathered tile: its first key index must not lie after the wave's rows;
-  //  - range tile: one of the 95 offsets between the wave's 32 rows and the tile's
-  //    64 keys must be kept (keys after a row give negative offsets, never kept), not
-  //    all 64 keys may be selected columns (the column pass covered those), and the
+  // Whether this wave has anything to do on tile t.
+  //  - gathered tile: its first key index (an aux word) must not lie after the wave's rows;
+  //  - range tile: one of the 95 offsets between the wave's 32 rows and the tile's 64
+  //    keys must be kept.  That depends on the tile diagonal and the wave only, not on
+  //    the query tile, so the list entry carries it as a bit per wave (bits 24..31; a
+  //    key after a row gives a negative offset, never kept).  Also not all 64 keys may
+  //    be selected columns (the column pass covered those: two aux words), and the
   //    tile must start before the sequence end.
-  auto act_words = [&](int t, int d, uint32_t& w0, uint32_t& w1, uint32_t& w2) {
+  // The aux words are read early (act_words) and looked at later (tile_active), so
+  // that the wait for them hides behind MFMAs.
+  auto act_words = [&](int t, uint32_t& w0, uint32_t& w1) {
     if (MODE != 2) return;
     const uint32_t* ax = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
     if (t < n_col_tiles) {
       w0 = ax[0];
     } else {
-      const int j0 = first_key(t, d);
-      const int wb = (P.off_max - (i0 - j0 + BQ - 1)) >> 5;
-      const int xs = P.off_max - (iw0 - j0 + 31);          // bit of the largest offset of the window
-      const int kk = (xs >> 5) - wb;                       // 0 .. 7
-      w0 = ax[kk + (lane & 3)];                            // lanes 0..3: the 4 words that hold the 95 bits
-      w1 = ax[16];
-      w2 = ax[17];
+      w0 = ax[16];
+      w1 = ax[17];
     }
   };
-  auto tile_active = [&](int t, int d, uint32_t w0, uint32_t w1, uint32_t w2) -> bool {
+  auto tile_active = [&](int t, int d, uint32_t w0, uint32_t w1) -> bool {
     bool act;
     const int j0 = first_key(t, d);
     if (is_col(t)) {
       act = (int)w0 <= iw0 + 31;
     } else if (MODE == 2) {
-      const int xs = P.off_max - (iw0 - j0 + 31);
-      const int lo = xs & 31;                              // window = bits [lo, lo + 95) of the 4 words
-      const int q = lane & 3;
-      const int b0 = max(lo - 32 * q, 0), b1 = min(lo + 95 - 32 * q, 32);   // bits of word q inside it
-      const uint32_t m = (b1 > b0) ? (uint32_t)(((1ull << (b1 - b0)) - 1ull) << b0) : 0u;
-      const bool hit = (lane < 4) && ((w0 & m) != 0u);
-      act = (__ballot(hit) != 0ull) && ((w1 & w2) != 0xFFFFFFFFu) && (j0 < S);
+      act = (((uint32_t)d >> (24 + wave)) & 1u) && ((w0 & w1) != 0xFFFFFFFFu) && (j0 < S);
     } else {
       act = j0 <= iw0 + 31;                        // else every key of the tile lies after the wave's rows
     }
@@ -575,9 +575,9 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     // A wave with nothing to do here looks at the next tile now, so that its next MFMA
     // phase knows at once whether it has work.
     if (!act_t && u + 1 < n_tiles) {
-      uint32_t w0 = 0, w1 = 0, w2 = 0;
-      act_words(u + 1, d_next, w0, w1, w2);
-      pre_act = tile_active(u + 1, d_next, w0, w1, w2);
+      uint32_t w0 = 0, w1 = 0;
+      act_words(u + 1, w0, w1);
+      pre_act = tile_active(u + 1, d_next, w0, w1);
       pre_done = true;
     }
   };
@@ -592,9 +592,9 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     const bool pv = WITH_V && act_t;
     bool act_n = false;
     if (pv) {
-      uint32_t aw0 = 0, aw1 = 0, aw2 = 0;
-      auto look = [&]() { if (have) act_words(u, dq0, aw0, aw1, aw2); };
-      auto decide = [&]() { act_n = have && tile_active(u, dq0, aw0, aw1, aw2); };
+      uint32_t aw0 = 0, aw1 = 0;
+      auto look = [&]() { if (have) act_words(u, aw0, aw1); };
+      auto decide = [&]() { act_n = have && tile_active(u, dq0, aw0, aw1); };
       mm_pv((u - 1) & (NSTAGE - 1), u & (NSTAGE - 1), setup_a, setup_v, setup_k, look, decide);
     } else {
       ahead_setup();
@@ -602,9 +602,9 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
         act_n = pre_act;
         if (act_n) warm_k(u & (NSTAGE - 1));
       } else if (have) {
-        uint32_t aw0 = 0, aw1 = 0, aw2 = 0;
-        act_words(u, dq0, aw0, aw1, aw2);
-        act_n = tile_active(u, dq0, aw0, aw1, aw2);
+        uint32_t aw0 = 0, aw1 = 0;
+        act_words(u, aw0, aw1);
+        act_n = tile_active(u, dq0, aw0, aw1);
         if (act_n) warm_k(u & (NSTAGE - 1));
       }
     }
@@ -644,19 +644,21 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   // time keeps the registers of both phases alive everywhere and spills.)
   if (grp == 0) {
     for (int n = 0; n <= n_tiles; ++n) {
+      // the scalar load is issued here and collected by the barrier's lgkmcnt(0): waited
+      // for anywhere else, it would drain the LDS reads in flight as well
+      const int dq4 = fetch_d(n + 4);
       mfma_phase(n);                         // n = 0: K Q^T(0) only; n = n_tiles: the last P V
       softmax_phase(n, dq0, dq1);
       wg_barrier();
-      const int dq4 = fetch_d(n + 4);        // in flight during the next iteration
       dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
     }
   } else {
     int dprev = 0;                           // tile diagonal of tile n - 1
     for (int n = 0; n <= n_tiles; ++n) {
+      const int dq4 = fetch_d(n + 4);
       softmax_phase(n - 1, dprev, dq0);
       mfma_phase(n);
       wg_barrier();
-      const int dq4 = fetch_d(n + 4);
       dprev = dq0; dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
     }
   }

@@ -107,7 +107,9 @@ __device__ bool any_offset(const uint32_t* ob, int off_max, int lo, int hi) {
 
 // Tile diagonal d pairs the 256-row query tile starting at row i0 with the
 // 64-key tile starting at key i0 + 192 - 64 d: it spans offsets
-// [64 d - 255, 64 d + 63].  dlist = ascending d with at least one kept offset.
+// [64 d - 255, 64 d + 63], the 32 rows of wave w (of 8) the 95 offsets from
+// 64 d - 255 + 32 w on.  dlist = ascending d with at least one kept offset; an
+// entry is d | (mask << 24), bit w of mask set when wave w sees a kept offset.
 __global__ __launch_bounds__(256) void dlist_kernel(MaskPrepParams P) {
   __shared__ int wave_cnt[4];
   __shared__ int base;
@@ -120,17 +122,20 @@ __global__ __launch_bounds__(256) void dlist_kernel(MaskPrepParams P) {
   __syncthreads();
   for (int d0 = 0; d0 < nd; d0 += 256) {
     int d = d0 + tid;
-    bool f = false;
+    uint32_t mask = 0;
     if (d < nd) {
-      int lo = max(0, 64 * d - 255), hi = min(P.S - 1, 64 * d + 63);
-      f = (lo <= hi) && any_offset(ob, P.off_max, lo, hi);
+      for (int w = 0; w < 8; ++w) {
+        int lo = max(0, 64 * d - 255 + 32 * w), hi = min(P.S - 1, 64 * d - 255 + 32 * w + 94);
+        if (lo <= hi && any_offset(ob, P.off_max, lo, hi)) mask |= 1u << w;
+      }
     }
+    const bool f = mask != 0;
     unsigned long long b = __ballot(f);
     if (lane == 0) wave_cnt[wave] = __popcll(b);
     __syncthreads();
     int pre = base;
     for (int w = 0; w < wave; ++w) pre += wave_cnt[w];
-    if (f) dl[pre + __popcll(b & ((1ull << lane) - 1ull))] = d;
+    if (f) dl[pre + __popcll(b & ((1ull << lane) - 1ull))] = (int32_t)((uint32_t)d | (mask << 24));
     __syncthreads();
     if (tid == 0) base += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
     __syncthreads();
