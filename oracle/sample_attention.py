@@ -23,6 +23,10 @@ What follows the paper, and where:
                         slash indices extended over the whole matrix and OR-ed.
 * ``masked_attn``     - Eq. 3 with c -> infinity (masked entries are exactly 0).
 * ``sample_attention``- Alg. 1 end to end (chunk_n = 1).
+* ``block_reduce``, ``block_mask``, ``block_masked_attn``,
+  ``block_sample_attention`` - the same algorithm at block granularity
+                        (Alg. 1 ``block_reduction`` with blk = 128, block
+                        filtering of Sec. 4.3, block-sparse mask of Fig. 6).
 * ``mask_diagnostics``- Sec. 3.3 (CRA = minimum kept probability mass over
                         queries) and Sec. 2.3 (sparsity ratio).
 
@@ -31,12 +35,23 @@ sort is descending; alpha is a fraction of the direction's total sampled mass;
 the cut uses ">="; alpha = 0 keeps nothing, alpha >= 1 keeps everything; ties
 go to the lower index; column j extends to all rows i >= j and offset o to all
 rows i >= o; the local window [0, w) is OR-ed in after selection; scores are
-kept per key / per offset (granularity 1) and per query head.
+kept per key / per offset (granularity 1) and per query head.  At block
+granularity the token-level column scores are summed over blocks of blk keys
+and the token-level slash scores over blocks of blk offsets; a selected block
+of offsets, extended over the matrix, is a band of blk diagonals, and the block
+mask keeps every blk x blk block (by block row and block column) that holds at
+least one pair (i, j) of a selected key block, of such a band, or of the local
+window, decided from the block indices alone (so the mask of a block depends
+only on its block column and on block row minus block column).
 
 Pins (tests/test_oracle_*.py): fp64 ``scaled_dot_product_attention`` on CPU for
 dense and banded cases, pure-Python brute force from the definitions on small
 inputs, the harmonic-number closed form for Q = 0, exhaustive subset
-enumeration for the selection, alpha = 1 == dense, alpha = 0 == sliding window.
+enumeration for the selection, alpha = 1 == dense, alpha = 0 == sliding window;
+for the block functions: blk = 1 reproduces the strip functions, block scores
+against sums over the explicit probability matrix, the block mask against a
+pure-Python cover of the token-level bands (kept blocks touch them, dropped
+blocks do not).
 """
 from __future__ import annotations
 
@@ -218,6 +233,98 @@ def sample_attention(q, k, v, n_sample_rows: int, alpha_c: float, alpha_s: float
     out, lse = masked_attn(q, k, v, I_c, I_s, window, scale, rows)
     return {"out": out, "lse": lse, "col": col, "slash": slash,
             "col_idx": I_c, "slash_idx": I_s, "sample_lse": lse_s}
+
+
+# ----------------------------------------------------------------------------
+# Block granularity (Alg. 1 block_reduction, blk = 128 in the paper)
+# ----------------------------------------------------------------------------
+def block_reduce(scores, blk: int) -> np.ndarray:
+    """A[b] = sum of scores[b*blk : (b+1)*blk] (the last block may be short)."""
+    s = _f64(scores)
+    if blk < 1:
+        raise ValueError("blk must be >= 1")
+    nb = (len(s) + blk - 1) // blk
+    return np.array([s[b * blk:(b + 1) * blk].sum() for b in range(nb)])
+
+
+def block_diagonals(S: int, slash_blocks, window: int, blk: int) -> np.ndarray:
+    """bool [n_blocks]: block diagonal delta (= block row - block column) is
+    kept when a full blk x blk block on it, which spans the offsets
+    blk*delta - (blk-1) .. blk*delta + (blk-1), holds a kept offset: one of a
+    selected offset block [blk*b, blk*b + blk) or of the window [0, w)."""
+    nb = (S + blk - 1) // blk
+    off_keep = np.zeros((nb + 2) * blk, dtype=bool)
+    for b in np.asarray(slash_blocks, dtype=np.int64):
+        off_keep[b * blk:(b + 1) * blk] = True
+    off_keep[: max(int(window), 0)] = True
+    keep = np.zeros(nb, dtype=bool)
+    for delta in range(nb):
+        lo, hi = max(blk * delta - (blk - 1), 0), blk * delta + (blk - 1)
+        keep[delta] = off_keep[lo:hi + 1].any()
+    return keep
+
+
+def block_mask(S: int, col_blocks, slash_blocks, window: int, blk: int, rows) -> np.ndarray:
+    """M[i, j] = (j <= i) and (block(j) in I_c or block(i) - block(j) on a kept
+    block diagonal), block(x) = x // blk."""
+    rows = np.asarray(rows, dtype=np.int64)
+    nb = (S + blk - 1) // blk
+    col_keep = np.zeros(nb, dtype=bool)
+    col_keep[np.asarray(col_blocks, dtype=np.int64)] = True
+    diag_keep = block_diagonals(S, slash_blocks, window, blk)
+    jb = np.arange(S) // blk
+    M = np.zeros((len(rows), S), dtype=bool)
+    for n, i in enumerate(rows):
+        ok = col_keep[jb[: i + 1]] | diag_keep[i // blk - jb[: i + 1]]
+        M[n, : i + 1] = ok
+    return M
+
+
+def block_masked_attn(q, k, v, col_blocks, slash_blocks, window: int, blk: int,
+                      scale: Optional[float] = None, rows=None):
+    """Eq. 3 with the block mask.  Returns (O [n_rows, d], lse [n_rows])."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    S, d = k.shape
+    sc = _scale(d, scale)
+    if window < 1:
+        raise ValueError("window must be >= 1 (every row keeps its diagonal)")
+    rows = np.arange(q.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
+    out = np.empty((len(rows), v.shape[1]))
+    lse = np.empty(len(rows))
+    at = 0
+    for r in _chunks(rows, 2 * S):
+        M = block_mask(S, col_blocks, slash_blocks, window, blk, r)
+        p, l = _causal_softmax_rows(q, k, r, sc, allowed=M)
+        out[at:at + len(r)] = p @ v
+        lse[at:at + len(r)] = l
+        at += len(r)
+    return out, lse
+
+
+def block_sample_attention(q, k, v, n_sample_rows: int, alpha_c: float, alpha_s: float,
+                           window: int, blk: int, scale: Optional[float] = None,
+                           rows=None) -> Dict[str, np.ndarray]:
+    """Alg. 1 end to end for one head with chunk_n = 1 at block granularity."""
+    col, slash, lse_s = sample_scores(q, k, n_sample_rows, scale)
+    A_c, A_s = block_reduce(col, blk), block_reduce(slash, blk)
+    I_c = select(A_c, alpha_c)
+    I_s = select(A_s, alpha_s)
+    out, lse = block_masked_attn(q, k, v, I_c, I_s, window, blk, scale, rows)
+    return {"out": out, "lse": lse, "col_block_scores": A_c, "slash_block_scores": A_s,
+            "col_blocks": I_c, "slash_blocks": I_s, "sample_lse": lse_s}
+
+
+def block_mask_density(S: int, col_blocks, slash_blocks, window: int, blk: int) -> float:
+    """Kept fraction of the blk x blk blocks of the causal triangle."""
+    nb = (S + blk - 1) // blk
+    col_keep = np.zeros(nb, dtype=bool)
+    col_keep[np.asarray(col_blocks, dtype=np.int64)] = True
+    diag_keep = block_diagonals(S, slash_blocks, window, blk)
+    kept = 0
+    for a in range(nb):
+        t = np.arange(a + 1)
+        kept += int(np.sum(col_keep[t] | diag_keep[a - t]))
+    return kept / (nb * (nb + 1) / 2.0)
 
 
 # ----------------------------------------------------------------------------
