@@ -12,6 +12,10 @@
  *   attend   sa_sparse_attn     flash-style attention over the merged mask
  *   baseline sa_dense_attn      dense causal flash-style attention (Eq. 1-2)
  *
+ * The same path at block granularity (Algorithm 1 "block_reduction", blk = 128
+ * in the paper): sa_sample_scores with granularity > 1 (or sa_block_scores on
+ * per-token scores), sa_select_blocks, sa_block_sparse_attn.
+ *
  * Conventions shared by every entry point
  * ---------------------------------------
  * - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
@@ -65,9 +69,11 @@ typedef struct {
 /* Stage-1 sampling.  n_sample_rows: the last n rows of the sequence are the
  * sampled queries (Algorithm 1 with chunk_n = 1), 1 <= n <= seq_len and a
  * multiple of 32 unless it equals seq_len.  n_chunks and granularity are the
- * paper's chunk_n and blk; this build implements n_chunks == 1 and
- * granularity == 1 (per-key / per-offset strips) and returns
- * SA_ERR_UNSUPPORTED otherwise. */
+ * paper's chunk_n and blk.  granularity 1 keeps scores per key / per offset;
+ * 64, 128 or 256 sums them over blocks of that many keys / offsets (multiples
+ * of the kernels' 64-key tile that divide their 256-row query tile; the paper
+ * uses 128).  This build implements n_chunks == 1 and these granularities
+ * and returns SA_ERR_UNSUPPORTED otherwise. */
 typedef struct {
   int32_t n_sample_rows;
   int32_t n_chunks;
@@ -80,11 +86,14 @@ typedef enum {
   SA_OP_SAMPLE_SCORES = 0,
   SA_OP_SELECT_STRIPS = 1,
   SA_OP_SPARSE_ATTN = 2,
-  SA_OP_DENSE_ATTN = 3
+  SA_OP_DENSE_ATTN = 3,
+  SA_OP_BLOCK_SPARSE_ATTN = 4
 } sa_op;
 
 /* Bytes of device workspace `op` needs for this shape (sampling may be NULL
- * for ops that do not sample).  Returns 0 for invalid arguments.  Host only. */
+ * for ops that neither sample nor work on blocks; SA_OP_BLOCK_SPARSE_ATTN
+ * reads sampling->granularity only).  Returns 0 for invalid arguments.
+ * Host only. */
 size_t sa_workspace_bytes(int op, const sa_shape* shape, const sa_sampling* sampling);
 
 /* 64 * ceil(ratio * seq_len / 64), clamped to [min(64, seq_len), seq_len]:
@@ -101,6 +110,11 @@ int32_t sa_rows_from_ratio(int32_t seq_len, float ratio);
  * out: col_scores, slash_scores  fp32 [batch*n_q_heads, seq_len]
  *      row_lse (nullable)        fp32 [batch*n_q_heads, n] natural-log
  *                                sum-exp of each sampled row
+ * With sampling->granularity = blk > 1 the outputs are the block scores of
+ * Algorithm 1's block_reduction instead, fp32 [batch*n_q_heads, n_blocks] with
+ * n_blocks = ceil(seq_len / blk):
+ *   col_scores[h, J]   = sum of the per-key scores of keys   [blk*J, blk*J + blk)
+ *   slash_scores[h, b] = sum of the per-offset scores of offsets [blk*b, blk*b + blk)
  * The sums are formed in a fixed order: repeated calls give identical bits.
  */
 sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
@@ -127,6 +141,48 @@ sa_status sa_select_strips(const sa_shape* shape,
                            int32_t* col_idx, int32_t* col_cnt,
                            int32_t* slash_idx, int32_t* slash_cnt,
                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Block granularity (Algorithm 1 block_reduction, Sec. 4.2-4.3; granularity is
+ * the paper's blk and must be 64, 128 or 256, n_blocks = ceil(seq_len / blk)).
+ *
+ * sa_block_scores: per-token scores [batch*n_q_heads, seq_len] -> block scores
+ * [batch*n_q_heads, n_blocks] as defined at sa_sample_scores (what that call
+ * does itself when sampling->granularity > 1).  No workspace.
+ *
+ * sa_select_blocks: sa_select_strips over the n_blocks candidates of each
+ * direction; index lists are int32 [batch*n_q_heads, n_blocks], ascending.
+ *
+ * sa_block_sparse_attn: attention under the block mask (Fig. 6: the selected
+ * blocks extended over the matrix and merged).  With block(x) = x / blk,
+ *   M[i, j] = (j <= i) and (block(j) in I_c[h]  or  block(i) - block(j) in D[h])
+ * where D holds the block diagonals on which a full blk x blk block contains
+ * a kept offset: b and b + 1 for every selected offset block b in I_s[h] (its
+ * offsets [blk*b, blk*b + blk) spread over both), and every delta with
+ * blk*delta - (blk - 1) <= local_window - 1 (delta = 0 always: local_window
+ * >= 1).  Kept blocks are computed whole; only the causal edge is masked.
+ * Lists: ascending, duplicate-free block indices in [0, n_blocks), counts in
+ * [0, n_blocks].  Outputs as for sa_sparse_attn.  Workspace:
+ * sa_workspace_bytes(SA_OP_BLOCK_SPARSE_ATTN, shape, sampling).
+ */
+sa_status sa_block_scores(const sa_shape* shape, int32_t granularity,
+                          const float* col_scores, const float* slash_scores,
+                          float* col_block_scores, float* slash_block_scores, void* stream);
+
+sa_status sa_select_blocks(const sa_shape* shape, int32_t granularity,
+                           const float* col_block_scores, const float* slash_block_scores,
+                           float alpha_c, float alpha_s,
+                           int32_t* col_blocks, int32_t* col_cnt,
+                           int32_t* slash_blocks, int32_t* slash_cnt,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+sa_status sa_block_sparse_attn(const sa_shape* shape, int32_t granularity,
+                               const void* q, const void* k, const void* v,
+                               const int32_t* col_blocks, const int32_t* col_cnt,
+                               const int32_t* slash_blocks, const int32_t* slash_cnt,
+                               int32_t local_window,
+                               void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Merge + attend (Algorithm 1 merge_index and sparse_flash_attn; Eq. 3 with

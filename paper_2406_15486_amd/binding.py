@@ -19,6 +19,7 @@ _LIB_NAME = "libsampleattn.so"
 
 SA_OUT_BF16, SA_OUT_F32 = 0, 1
 SA_OP_SAMPLE_SCORES, SA_OP_SELECT_STRIPS, SA_OP_SPARSE_ATTN, SA_OP_DENSE_ATTN = 0, 1, 2, 3
+SA_OP_BLOCK_SPARSE_ATTN = 4
 
 
 class SaError(RuntimeError):
@@ -91,6 +92,14 @@ def load_library() -> ctypes.CDLL:
     lib.sa_sparse_attn.restype = ctypes.c_int
     lib.sa_sparse_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, i32p, i32p, i32p, i32p,
                                    ctypes.c_int32, vp, ctypes.c_int, f32p, vp, vp, ctypes.c_size_t, vp]
+    lib.sa_block_scores.restype = ctypes.c_int
+    lib.sa_block_scores.argtypes = [ctypes.POINTER(_CShape), ctypes.c_int32, f32p, f32p, f32p, f32p, vp]
+    lib.sa_select_blocks.restype = ctypes.c_int
+    lib.sa_select_blocks.argtypes = [ctypes.POINTER(_CShape), ctypes.c_int32, f32p, f32p, ctypes.c_float,
+                                     ctypes.c_float, i32p, i32p, i32p, i32p, vp, ctypes.c_size_t, vp]
+    lib.sa_block_sparse_attn.restype = ctypes.c_int
+    lib.sa_block_sparse_attn.argtypes = [ctypes.POINTER(_CShape), ctypes.c_int32, vp, vp, vp, i32p, i32p, i32p, i32p,
+                                         ctypes.c_int32, vp, ctypes.c_int, f32p, vp, vp, ctypes.c_size_t, vp]
     lib.sa_dense_attn.restype = ctypes.c_int
     lib.sa_dense_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p,
                                   vp, ctypes.c_size_t, vp]
@@ -132,10 +141,14 @@ def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
-def sa_workspace_bytes(op: int, shape: Shape, n_sample_rows: int = 0) -> int:
+def n_blocks(seq_len: int, granularity: int) -> int:
+    return (seq_len + granularity - 1) // granularity
+
+
+def sa_workspace_bytes(op: int, shape: Shape, n_sample_rows: int = 0, granularity: int = 1) -> int:
     lib = load_library()
     cs = shape.c()
-    sm = _CSampling(n_sample_rows, 1, 1)
+    sm = _CSampling(n_sample_rows, 1, granularity)
     return int(lib.sa_workspace_bytes(op, ctypes.byref(cs), ctypes.byref(sm)))
 
 
@@ -144,17 +157,19 @@ def sa_rows_from_ratio(seq_len: int, ratio: float) -> int:
 
 
 # -------------------------------------------------------------- entry points --
-def sa_sample_scores(q, k, n_sample_rows: int, scale: float = 0.0, workspace=None, want_lse=False):
+def sa_sample_scores(q, k, n_sample_rows: int, scale: float = 0.0, workspace=None, want_lse=False,
+                     granularity: int = 1):
     """Stage 1: column and slash scores of the last ``n_sample_rows`` queries.
-    Returns (col [B*Hq, S] f32, slash [B*Hq, S] f32[, row_lse [B*Hq, n] f32])."""
+    Returns (col [B*Hq, S] f32, slash [B*Hq, S] f32[, row_lse [B*Hq, n] f32]);
+    with granularity > 1 the two score tensors are [B*Hq, ceil(S / granularity)]."""
     lib = load_library()
     sh = _shape_of(q, k, scale)
     _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
     _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
-    cs, sm = sh.c(), _CSampling(n_sample_rows, 1, 1)
+    cs, sm = sh.c(), _CSampling(n_sample_rows, 1, granularity)
     need = int(lib.sa_workspace_bytes(SA_OP_SAMPLE_SCORES, ctypes.byref(cs), ctypes.byref(sm)))
     ws = workspace if workspace is not None else _workspace(need, q.device)
-    col = torch.empty(sh.n_bh, sh.seq_len, dtype=torch.float32, device=q.device)
+    col = torch.empty(sh.n_bh, n_blocks(sh.seq_len, max(granularity, 1)), dtype=torch.float32, device=q.device)
     slash = torch.empty_like(col)
     lse = torch.empty(sh.n_bh, max(n_sample_rows, 1), dtype=torch.float32, device=q.device) if want_lse else None
     st = lib.sa_sample_scores(ctypes.byref(cs), ctypes.byref(sm), _ptr(q), _ptr(k), _ptr(col), _ptr(slash),
@@ -182,6 +197,72 @@ def sa_select_strips(col_scores, slash_scores, alpha_c: float, alpha_s: float, s
     if st != 0:
         raise SaError(st, "sa_select_strips")
     return col_idx, col_cnt, slash_idx, slash_cnt
+
+
+def sa_block_scores(col_scores, slash_scores, granularity: int, shape: Shape):
+    """Per-token scores -> block scores (Algorithm 1 block_reduction)."""
+    lib = load_library()
+    _check(col_scores, torch.float32, (shape.n_bh, shape.seq_len), "col_scores")
+    _check(slash_scores, torch.float32, (shape.n_bh, shape.seq_len), "slash_scores")
+    nb = n_blocks(shape.seq_len, max(granularity, 1))
+    cb = torch.empty(shape.n_bh, nb, dtype=torch.float32, device=col_scores.device)
+    sb = torch.empty_like(cb)
+    cs = shape.c()
+    st = lib.sa_block_scores(ctypes.byref(cs), int(granularity), _ptr(col_scores), _ptr(slash_scores),
+                             _ptr(cb), _ptr(sb), _stream())
+    if st != 0:
+        raise SaError(st, "sa_block_scores")
+    return cb, sb
+
+
+def sa_select_blocks(col_block_scores, slash_block_scores, alpha_c: float, alpha_s: float, granularity: int,
+                     shape: Shape):
+    """Stage 2 over blocks: (col_blocks, col_cnt, slash_blocks, slash_cnt) int32 device tensors."""
+    lib = load_library()
+    nb = n_blocks(shape.seq_len, max(granularity, 1))
+    _check(col_block_scores, torch.float32, (shape.n_bh, nb), "col_block_scores")
+    _check(slash_block_scores, torch.float32, (shape.n_bh, nb), "slash_block_scores")
+    dev = col_block_scores.device
+    col_blk = torch.empty(shape.n_bh, nb, dtype=torch.int32, device=dev)
+    slash_blk = torch.empty_like(col_blk)
+    col_cnt = torch.empty(shape.n_bh, dtype=torch.int32, device=dev)
+    slash_cnt = torch.empty_like(col_cnt)
+    cs = shape.c()
+    st = lib.sa_select_blocks(ctypes.byref(cs), int(granularity), _ptr(col_block_scores), _ptr(slash_block_scores),
+                              ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
+                              _ptr(col_blk), _ptr(col_cnt), _ptr(slash_blk), _ptr(slash_cnt), None, 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_select_blocks")
+    return col_blk, col_cnt, slash_blk, slash_cnt
+
+
+def sa_block_sparse_attn(q, k, v, col_blocks, col_cnt, slash_blocks, slash_cnt, local_window: int,
+                         granularity: int, scale: float = 0.0, out_dtype: int = SA_OUT_BF16, workspace=None,
+                         want_lse: bool = False, want_tiles: bool = False):
+    """Attention under the block mask.  Returns (out, lse or None, tiles or None)."""
+    lib = load_library()
+    sh = _shape_of(q, k, scale)
+    _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
+    _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
+    _check(v, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "v")
+    nb = n_blocks(sh.seq_len, max(granularity, 1))
+    for t, nm in ((col_blocks, "col_blocks"), (slash_blocks, "slash_blocks")):
+        _check(t, torch.int32, (sh.n_bh, nb), nm)
+    for t, nm in ((col_cnt, "col_cnt"), (slash_cnt, "slash_cnt")):
+        _check(t, torch.int32, (sh.n_bh,), nm)
+    cs, sm = sh.c(), _CSampling(0, 1, granularity)
+    need = int(lib.sa_workspace_bytes(SA_OP_BLOCK_SPARSE_ATTN, ctypes.byref(cs), ctypes.byref(sm)))
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    out = torch.empty(q.shape, dtype=torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16, device=q.device)
+    lse = torch.empty(sh.n_bh, sh.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
+    tiles = torch.empty(sh.n_bh, dtype=torch.int64, device=q.device) if want_tiles else None
+    st = lib.sa_block_sparse_attn(ctypes.byref(cs), int(granularity), _ptr(q), _ptr(k), _ptr(v),
+                                  _ptr(col_blocks), _ptr(col_cnt), _ptr(slash_blocks), _ptr(slash_cnt),
+                                  int(local_window), _ptr(out), out_dtype, _ptr(lse), _ptr(tiles), _ptr(ws),
+                                  ws.numel() if ws is not None else 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_block_sparse_attn")
+    return out, lse, tiles
 
 
 def sa_sparse_attn(q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window: int,
@@ -255,16 +336,20 @@ class SampleAttentionPlan:
     lists and the output are allocated once, so a step is three library calls
     and nothing else (no allocation, no host synchronisation)."""
 
-    def __init__(self, shape: Shape, n_sample_rows: int, device="cuda", out_dtype: int = SA_OUT_BF16):
+    def __init__(self, shape: Shape, n_sample_rows: int, device="cuda", out_dtype: int = SA_OUT_BF16,
+                 granularity: int = 1):
         lib = load_library()
         self.lib, self.shape, self.n_s, self.out_dtype = lib, shape, n_sample_rows, out_dtype
+        self.granularity = granularity
         self.cs = shape.c()
-        self.sm = _CSampling(n_sample_rows, 1, 1)
-        need = max(int(lib.sa_workspace_bytes(op, ctypes.byref(self.cs), ctypes.byref(self.sm)))
-                   for op in (SA_OP_SAMPLE_SCORES, SA_OP_SPARSE_ATTN, SA_OP_DENSE_ATTN))
-        if need == 0:
+        self.sm = _CSampling(n_sample_rows, 1, granularity)
+        ops = (SA_OP_SAMPLE_SCORES, SA_OP_SPARSE_ATTN if granularity == 1 else SA_OP_BLOCK_SPARSE_ATTN,
+               SA_OP_DENSE_ATTN)
+        sizes = [int(lib.sa_workspace_bytes(op, ctypes.byref(self.cs), ctypes.byref(self.sm))) for op in ops]
+        if min(sizes) == 0:
             raise ValueError("invalid shape or sampling for this library")
-        n, S = shape.n_bh, shape.seq_len
+        need = max(sizes)
+        n, S = shape.n_bh, n_blocks(shape.seq_len, granularity)   # candidates per head and direction
         self.ws = torch.empty(need, dtype=torch.uint8, device=device)
         self.col = torch.empty(n, S, dtype=torch.float32, device=device)
         self.slash = torch.empty_like(self.col)
@@ -274,7 +359,7 @@ class SampleAttentionPlan:
         self.slash_cnt = torch.empty_like(self.col_cnt)
         self.tiles = torch.zeros(n, dtype=torch.int64, device=device)
         odt = torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16
-        self.out = torch.empty(shape.batch, shape.n_q_heads, S, shape.head_dim, dtype=odt, device=device)
+        self.out = torch.empty(shape.batch, shape.n_q_heads, shape.seq_len, shape.head_dim, dtype=odt, device=device)
 
     def _ok(self, st, where):
         if st != 0:
@@ -286,12 +371,25 @@ class SampleAttentionPlan:
                                            self.ws.numel(), _stream()), "sa_sample_scores")
 
     def select(self, alpha_c, alpha_s):
+        if self.granularity != 1:
+            self._ok(self.lib.sa_select_blocks(ctypes.byref(self.cs), self.granularity, _ptr(self.col),
+                                               _ptr(self.slash), ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
+                                               _ptr(self.col_idx), _ptr(self.col_cnt), _ptr(self.slash_idx),
+                                               _ptr(self.slash_cnt), None, 0, _stream()), "sa_select_blocks")
+            return
         self._ok(self.lib.sa_select_strips(ctypes.byref(self.cs), _ptr(self.col), _ptr(self.slash),
                                            ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
                                            _ptr(self.col_idx), _ptr(self.col_cnt), _ptr(self.slash_idx),
                                            _ptr(self.slash_cnt), None, 0, _stream()), "sa_select_strips")
 
     def attend(self, q, k, v, window):
+        if self.granularity != 1:
+            self._ok(self.lib.sa_block_sparse_attn(ctypes.byref(self.cs), self.granularity, _ptr(q), _ptr(k), _ptr(v),
+                                                   _ptr(self.col_idx), _ptr(self.col_cnt), _ptr(self.slash_idx),
+                                                   _ptr(self.slash_cnt), int(window), _ptr(self.out),
+                                                   self.out_dtype, None, _ptr(self.tiles), _ptr(self.ws),
+                                                   self.ws.numel(), _stream()), "sa_block_sparse_attn")
+            return
         self._ok(self.lib.sa_sparse_attn(ctypes.byref(self.cs), _ptr(q), _ptr(k), _ptr(v), _ptr(self.col_idx),
                                          _ptr(self.col_cnt), _ptr(self.slash_idx), _ptr(self.slash_cnt),
                                          int(window), _ptr(self.out), self.out_dtype, None, _ptr(self.tiles),
@@ -317,4 +415,14 @@ def sample_attention(q, k, v, n_sample_rows: int, alpha_c: float, alpha_s: float
     col, slash = sa_sample_scores(q, k, n_sample_rows, scale)
     ci, cc, si, sc = sa_select_strips(col, slash, alpha_c, alpha_s, sh)
     out, _, _ = sa_sparse_attn(q, k, v, ci, cc, si, sc, local_window, scale, out_dtype)
+    return out
+
+
+def block_sample_attention(q, k, v, n_sample_rows: int, alpha_c: float, alpha_s: float, local_window: int,
+                           granularity: int = 128, scale: float = 0.0, out_dtype: int = SA_OUT_BF16):
+    """The whole path at block granularity (Algorithm 1 with blk = granularity)."""
+    sh = _shape_of(q, k, scale)
+    cb, sb = sa_sample_scores(q, k, n_sample_rows, scale, granularity=granularity)
+    ci, cc, si, sc = sa_select_blocks(cb, sb, alpha_c, alpha_s, granularity, sh)
+    out, _, _ = sa_block_sparse_attn(q, k, v, ci, cc, si, sc, local_window, granularity, scale, out_dtype)
     return out

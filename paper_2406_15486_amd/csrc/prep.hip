@@ -4,7 +4,9 @@
 //    into compact per-head arrays (Algorithm 1, merge_index: column strips);
 //  - mask_prep: the selected columns and offsets (plus the local window) as
 //    bitmaps, and the list of 64-key tile diagonals that hold at least one kept
-//    offset (Algorithm 1, merge_index: slash strips extended over the matrix).
+//    offset (Algorithm 1, merge_index: slash strips extended over the matrix);
+//  - block granularity (Algorithm 1, block_reduction with blk > 1): token scores
+//    summed over blocks, and the block lists turned into the same metadata.
 #include "sa_device.h"
 #include "sa_kernels.h"
 
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256) void set_bits_kernel(MaskPrepParams P) {
     int j = P.col_idx[(size_t)h * P.S + c];
     if (j >= 0 && j < P.S) atomicOr(cb + (j >> 5), 1u << (j & 31));
   }
-  if (c < P.S && c < P.slash_cnt[h]) {
+  if (P.slash_idx != nullptr && c < P.S && c < P.slash_cnt[h]) {
     int o = P.slash_idx[(size_t)h * P.S + c];
     if (o >= 0 && o < P.S) {
       int x = P.off_max - o;
@@ -143,7 +145,142 @@ __global__ __launch_bounds__(256) void dlist_kernel(MaskPrepParams P) {
   if (tid == 0) P.dcnt[h] = base;
 }
 
+// ---- block granularity ----------------------------------------------------------
+// out[g][b] = sum of in[g][b*blk .. (b+1)*blk) (the last block may be short): one
+// wave per block, lanes stride the block, fp64 partial sums combined in a fixed
+// butterfly order, so the result does not depend on the launch.
+__global__ __launch_bounds__(256) void block_reduce_kernel(const float* in, float* out, int S, int blk, int nb) {
+  const int g = blockIdx.y;
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (b >= nb) return;
+  const float* src = in + (size_t)g * S;
+  const int lo = b * blk, hi = min(lo + blk, S);
+  double acc = 0.0;
+  for (int e = lo + lane; e < hi; e += 64) acc += (double)src[e];
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (lane == 0) out[(size_t)g * nb + b] = (float)acc;
+}
+
+__device__ __forceinline__ int floor_div(int x, int y) { return x >= 0 ? x / y : -((-x + y - 1) / y); }
+
+// selected key blocks -> the token columns they hold (ascending, as the strip path
+// wants them).  Only the last block of the sequence can be short, and an ascending
+// list has it last, so token slot c belongs to list entry c / blk.
+__global__ __launch_bounds__(256) void expand_blocks_kernel(BlockPrepParams P) {
+  const int h = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int cnt = min(max(P.col_bcnt[h], 0), P.nb);
+  const int32_t* bl = P.col_blk + (size_t)h * P.nb;
+  if (c == 0) {
+    int n = 0;
+    if (cnt > 0) {
+      int last = min(max(bl[cnt - 1], 0), P.nb - 1);
+      n = (cnt - 1) * P.blk + min(P.blk, P.S - last * P.blk);
+    }
+    P.tok_cnt[h] = min(n, P.S);
+  }
+  if (c >= P.S) return;
+  const int r = c / P.blk;
+  int j = 0x7FFFFFFF;
+  if (r < cnt) {
+    int J = min(max(bl[r], 0), P.nb - 1);   // a malformed list must not lead out of bounds
+    j = min(J * P.blk + c % P.blk, P.S - 1);
+  }
+  P.tok_idx[(size_t)h * P.S + c] = j;
+}
+
+// kept block diagonals (block row minus block column): a full block on diagonal
+// delta spans the offsets blk*delta - (blk-1) .. blk*delta + (blk-1), so a selected
+// block b of offsets [blk*b, blk*b + blk) lies on diagonals b and b + 1, and the
+// window [0, w) on every diagonal with blk*delta - (blk-1) <= w - 1.
+__global__ __launch_bounds__(256) void diag_bits_kernel(BlockPrepParams P) {
+  const int h = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  uint32_t* db = P.diag_bits + (size_t)h * P.db_words;
+  const int cnt = min(max(P.slash_bcnt[h], 0), P.nb);
+  if (c < cnt) {
+    int b = P.slash_blk[(size_t)h * P.nb + c];
+    if (b >= 0 && b < P.nb) {
+      atomicOr(db + (b >> 5), 1u << (b & 31));
+      atomicOr(db + ((b + 1) >> 5), 1u << ((b + 1) & 31));
+    }
+  }
+  if (c <= P.nb && (long long)c * P.blk - (P.blk - 1) <= (long long)P.window - 1)
+    atomicOr(db + (c >> 5), 1u << (c & 31));
+}
+
+// The tile-diagonal list of the block mask.  With 256-row query tiles, 64-key tiles
+// and blk in {64, 128, 256}, the 32 rows of wave w lie in one row block and the key
+// tile of tile diagonal d in one column block, floor(32 w / blk) - floor((192 - 64 d)
+// / blk) block diagonals apart whatever the query tile: the entry format is that of
+// dlist_kernel, the per-wave bit now saying "this wave's block is kept".
+__global__ __launch_bounds__(256) void dlist_block_kernel(BlockPrepParams P) {
+  __shared__ int wave_cnt[4];
+  __shared__ int base;
+  const int h = blockIdx.x;
+  const uint32_t* db = P.diag_bits + (size_t)h * P.db_words;
+  int32_t* dl = P.dlist + (size_t)h * P.dlist_stride;
+  const int nd = (P.S + 63) / 64 + 3;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) base = 0;
+  __syncthreads();
+  for (int d0 = 0; d0 < nd; d0 += 256) {
+    int d = d0 + tid;
+    uint32_t mask = 0;
+    if (d < nd) {
+      const int kb = floor_div(192 - 64 * d, P.blk);
+      for (int w = 0; w < 8; ++w) {
+        const int delta = (32 * w) / P.blk - kb;
+        const int o_lo = 64 * d - 255 + 32 * w, o_hi = o_lo + 94;   // offsets the wave meets on this tile
+        if (delta >= 0 && delta <= P.nb && o_hi >= 0 && o_lo <= P.S - 1 && ((db[delta >> 5] >> (delta & 31)) & 1u))
+          mask |= 1u << w;
+      }
+    }
+    const bool f = mask != 0;
+    unsigned long long b = __ballot(f);
+    if (lane == 0) wave_cnt[wave] = __popcll(b);
+    __syncthreads();
+    int pre = base;
+    for (int w = 0; w < wave; ++w) pre += wave_cnt[w];
+    if (f) dl[pre + __popcll(b & ((1ull << lane) - 1ull))] = (int32_t)((uint32_t)d | (mask << 24));
+    __syncthreads();
+    if (tid == 0) base += wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    __syncthreads();
+  }
+  if (tid == 0) P.dcnt[h] = base;
+}
+
 }  // namespace
+
+hipError_t launch_block_reduce(const float* in, float* out, int n_rows, int S, int blk, hipStream_t st) {
+  const int nb = (S + blk - 1) / blk;
+  if (n_rows == 0 || nb == 0) return hipSuccess;
+  hipLaunchKernelGGL(block_reduce_kernel, dim3((nb + 3) / 4, n_rows), dim3(256), 0, st, in, out, S, blk, nb);
+  return hipGetLastError();
+}
+
+// Block lists -> the metadata of the strip path: token columns of the selected key
+// blocks (tok_idx / tok_cnt), their bitmap, every offset >= 0 kept inside a computed
+// tile (the kept blocks are kept whole), and the tile-diagonal list.
+hipError_t launch_block_prep(const BlockPrepParams& P, hipStream_t st) {
+  size_t ncb = (size_t)P.n_bh * P.cb_words, nob = (size_t)P.n_bh * P.rb_words, ndb = (size_t)P.n_bh * P.db_words;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, P.col_bits, ncb, 0u);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, P.off_bits, nob, 0u);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, P.diag_bits, ndb, 0u);
+  dim3 grid((P.S + 255) / 256, P.n_bh);
+  hipLaunchKernelGGL(expand_blocks_kernel, grid, dim3(256), 0, st, P);
+  hipLaunchKernelGGL(diag_bits_kernel, dim3((P.nb + 256) / 256, P.n_bh), dim3(256), 0, st, P);
+  MaskPrepParams M;
+  M.col_idx = P.tok_idx; M.col_cnt = P.tok_cnt; M.slash_idx = nullptr; M.slash_cnt = nullptr;
+  M.col_bits = P.col_bits; M.off_bits = P.off_bits; M.dlist = P.dlist; M.dcnt = P.dcnt;
+  M.n_bh = P.n_bh; M.S = P.S; M.window = P.S;   // offsets 0 .. S-1: all kept
+  M.cb_words = P.cb_words; M.rb_words = P.rb_words; M.dlist_stride = P.dlist_stride; M.off_max = P.off_max;
+  hipLaunchKernelGGL(set_bits_kernel, grid, dim3(256), 0, st, M);
+  hipLaunchKernelGGL(dlist_block_kernel, dim3(P.n_bh), dim3(256), 0, st, P);
+  return hipGetLastError();
+}
 
 hipError_t launch_gather_transpose(const GatherParams& P, hipStream_t st) {
   dim3 grid(P.C_pad / 64, P.n_out);

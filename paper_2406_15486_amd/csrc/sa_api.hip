@@ -35,11 +35,19 @@ sa_status check_shape(const sa_shape* s, Dims* d) {
   return SA_OK;
 }
 
+// block sizes the block path is built for: multiples of the 64-key tile that divide
+// the 256-row query tile (the paper fixes blk = 128)
+sa_status check_granularity(int g) {
+  if (g < 1) return SA_ERR_INVALID_ARG;
+  return (g == 64 || g == 128 || g == 256) ? SA_OK : SA_ERR_UNSUPPORTED;
+}
+
 sa_status check_sampling(const sa_sampling* sm, const Dims& d) {
   if (sm == nullptr) return SA_ERR_INVALID_ARG;
   if (sm->n_sample_rows < 1 || sm->n_sample_rows > d.S) return SA_ERR_INVALID_ARG;
   if (sm->n_chunks < 1 || sm->granularity < 1) return SA_ERR_INVALID_ARG;
-  if (sm->n_chunks != 1 || sm->granularity != 1) return SA_ERR_UNSUPPORTED;
+  if (sm->n_chunks != 1) return SA_ERR_UNSUPPORTED;
+  if (sm->granularity != 1 && check_granularity(sm->granularity) != SA_OK) return SA_ERR_UNSUPPORTED;
   if (sm->n_sample_rows % 32 != 0 && sm->n_sample_rows != d.S) return SA_ERR_INVALID_ARG;
   return SA_OK;
 }
@@ -52,12 +60,17 @@ sa_status check_ws(const void* ws, size_t have, size_t need) {
 }
 
 // ---- workspace layouts --------------------------------------------------------
-struct SampleWs { size_t lse, partial, total; };
-SampleWs sample_ws(const Dims& d, int n_s) {
+struct SampleWs { size_t lse, partial, tok_col, tok_slash, total; };
+SampleWs sample_ws(const Dims& d, int n_s, int granularity) {
   SampleWs w;
   size_t at = 0;
   w.lse = at;     at += align_up((size_t)d.n_bh * n_s * sizeof(float));
   w.partial = at; at += align_up(sa::score_partial_floats(d.S, n_s, d.n_bh) * sizeof(float));
+  w.tok_col = w.tok_slash = at;
+  if (granularity > 1) {   // per-token scores, reduced to blocks afterwards
+    w.tok_col = at;   at += align_up((size_t)d.n_bh * d.S * sizeof(float));
+    w.tok_slash = at; at += align_up((size_t)d.n_bh * d.S * sizeof(float));
+  }
   w.total = at;
   return w;
 }
@@ -81,6 +94,20 @@ SparseWs sparse_ws(const Dims& d) {
   w.obits = at; at += align_up((size_t)d.n_bh * w.rb_words * 4);
   w.dlist = at; at += align_up((size_t)d.n_bh * w.dlist_stride * 4);
   w.dcnt = at;  at += align_up((size_t)d.n_bh * 4);
+  w.total = at;
+  return w;
+}
+
+struct BlockWs { SparseWs sp; size_t tok_idx, tok_cnt, dbits, total; int nb, db_words; };
+BlockWs block_ws(const Dims& d, int blk) {
+  BlockWs w;
+  w.sp = sparse_ws(d);
+  w.nb = (d.S + blk - 1) / blk;
+  w.db_words = (w.nb + 1) / 32 + 1;
+  size_t at = w.sp.total;
+  w.tok_idx = at; at += align_up((size_t)d.n_bh * d.S * 4);
+  w.tok_cnt = at; at += align_up((size_t)d.n_bh * 4);
+  w.dbits = at;   at += align_up((size_t)d.n_bh * w.db_words * 4);
   w.total = at;
   return w;
 }
@@ -145,10 +172,13 @@ size_t sa_workspace_bytes(int op, const sa_shape* shape, const sa_sampling* samp
   switch (op) {
     case SA_OP_SAMPLE_SCORES:
       if (check_sampling(sampling, d) != SA_OK) return 0;
-      return sample_ws(d, sampling->n_sample_rows).total;
+      return sample_ws(d, sampling->n_sample_rows, sampling->granularity).total;
     case SA_OP_SELECT_STRIPS: return 0;
     case SA_OP_SPARSE_ATTN: return sparse_ws(d).total;
     case SA_OP_DENSE_ATTN: return dense_ws(d);
+    case SA_OP_BLOCK_SPARSE_ATTN:
+      if (sampling == nullptr || check_granularity(sampling->granularity) != SA_OK) return 0;
+      return block_ws(d, sampling->granularity).total;
     default: return 0;
   }
 }
@@ -172,12 +202,15 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   if (s != SA_OK) return s;
   if (q == nullptr || k == nullptr || col_scores == nullptr || slash_scores == nullptr) return SA_ERR_INVALID_ARG;
   const int n_s = sampling->n_sample_rows;
-  SampleWs w = sample_ws(d, n_s);
+  const int blk = sampling->granularity;
+  SampleWs w = sample_ws(d, n_s, blk);
   s = check_ws(workspace, workspace_bytes, w.total);
   if (s != SA_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
   float* lse = row_lse ? row_lse : reinterpret_cast<float*>(ws + w.lse);
+  float* tok_col = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_col) : col_scores;
+  float* tok_slash = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_slash) : slash_scores;
 
   // pass 1: log-sum-exp of every sampled row (flash sweep without V)
   sa::FlashParams P = base_flash(d, q, k);
@@ -197,7 +230,7 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   C.q = static_cast<const uint16_t*>(q);
   C.k = static_cast<const uint16_t*>(k);
   C.lse = lse;
-  C.col = col_scores; C.slash = slash_scores;
+  C.col = tok_col; C.slash = tok_slash;
   C.partial = reinterpret_cast<float*>(ws + w.partial);
   C.S = d.S; C.n_s = n_s; C.n_bh = d.n_bh; C.n_bkv = d.n_bkv; C.group = d.group;
   C.scale_log2 = P.scale_log2;
@@ -207,19 +240,47 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   }
   if (s != SA_OK) return s;
   Scope sc(SA_K_SCORE_FINAL, st);
-  return dev(sa::launch_score_finalize(C, st));
+  s = dev(sa::launch_score_finalize(C, st));
+  if (s != SA_OK || blk == 1) return s;
+  // block_reduction: the per-token scores summed over blocks of blk keys / offsets
+  s = dev(sa::launch_block_reduce(tok_col, col_scores, d.n_bh, d.S, blk, st));
+  if (s != SA_OK) return s;
+  return dev(sa::launch_block_reduce(tok_slash, slash_scores, d.n_bh, d.S, blk, st));
 }
 
-sa_status sa_select_strips(const sa_shape* shape,
-                           const float* col_scores, const float* slash_scores,
-                           float alpha_c, float alpha_s,
-                           int32_t* col_idx, int32_t* col_cnt,
-                           int32_t* slash_idx, int32_t* slash_cnt,
-                           void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace; (void)workspace_bytes;
+sa_status sa_block_scores(const sa_shape* shape, int32_t granularity,
+                          const float* col_scores, const float* slash_scores,
+                          float* col_block_scores, float* slash_block_scores, void* stream) {
   Dims d;
   sa_status s = check_shape(shape, &d);
   if (s != SA_OK) return s;
+  s = check_granularity(granularity);
+  if (s != SA_OK) return s;
+  if (col_scores == nullptr || slash_scores == nullptr || col_block_scores == nullptr || slash_block_scores == nullptr)
+    return SA_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Scope sc(SA_K_SCORE_FINAL, st);
+  s = dev(sa::launch_block_reduce(col_scores, col_block_scores, d.n_bh, d.S, granularity, st));
+  if (s != SA_OK) return s;
+  return dev(sa::launch_block_reduce(slash_scores, slash_block_scores, d.n_bh, d.S, granularity, st));
+}
+
+}  // extern "C"
+
+namespace {
+// both selections over n candidates per head (keys / offsets, or blocks of them)
+sa_status select_both(const sa_shape* shape, int granularity,
+                      const float* col_scores, const float* slash_scores,
+                      float alpha_c, float alpha_s,
+                      int32_t* col_idx, int32_t* col_cnt,
+                      int32_t* slash_idx, int32_t* slash_cnt, void* stream) {
+  Dims d;
+  sa_status s = check_shape(shape, &d);
+  if (s != SA_OK) return s;
+  if (granularity != 1) {
+    s = check_granularity(granularity);
+    if (s != SA_OK) return s;
+  }
   if (col_scores == nullptr || slash_scores == nullptr || col_idx == nullptr || col_cnt == nullptr ||
       slash_idx == nullptr || slash_cnt == nullptr)
     return SA_ERR_INVALID_ARG;
@@ -228,30 +289,67 @@ sa_status sa_select_strips(const sa_shape* shape,
   hipStream_t st = static_cast<hipStream_t>(stream);
   Scope sc(SA_K_SELECT, st);
   sa::SelectParams P;
-  P.n_prob = d.n_bh; P.S = d.S;
+  P.n_prob = d.n_bh; P.S = (d.S + granularity - 1) / granularity;
   P.scores = col_scores; P.idx = col_idx; P.cnt = col_cnt; P.alpha = alpha_c;
   s = dev(sa::launch_select(P, st));
   if (s != SA_OK) return s;
   P.scores = slash_scores; P.idx = slash_idx; P.cnt = slash_cnt; P.alpha = alpha_s;
   return dev(sa::launch_select(P, st));
 }
+}  // namespace
 
-sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
-                         const int32_t* col_idx, const int32_t* col_cnt,
-                         const int32_t* slash_idx, const int32_t* slash_cnt,
-                         int32_t local_window,
-                         void* out, int out_dtype, float* out_lse, uint64_t* tiles,
-                         void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" {
+
+sa_status sa_select_strips(const sa_shape* shape,
+                           const float* col_scores, const float* slash_scores,
+                           float alpha_c, float alpha_s,
+                           int32_t* col_idx, int32_t* col_cnt,
+                           int32_t* slash_idx, int32_t* slash_cnt,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  return select_both(shape, 1, col_scores, slash_scores, alpha_c, alpha_s, col_idx, col_cnt, slash_idx, slash_cnt,
+                     stream);
+}
+
+sa_status sa_select_blocks(const sa_shape* shape, int32_t granularity,
+                           const float* col_block_scores, const float* slash_block_scores,
+                           float alpha_c, float alpha_s,
+                           int32_t* col_blocks, int32_t* col_cnt,
+                           int32_t* slash_blocks, int32_t* slash_cnt,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (granularity < 1) return SA_ERR_INVALID_ARG;
+  if (granularity == 1) return SA_ERR_UNSUPPORTED;   // per-token selection is sa_select_strips
+  return select_both(shape, granularity, col_block_scores, slash_block_scores, alpha_c, alpha_s, col_blocks, col_cnt,
+                     slash_blocks, slash_cnt, stream);
+}
+
+}  // extern "C"
+
+namespace {
+// granularity 1: strip lists (per key / per offset); otherwise lists of blocks
+sa_status sparse_attn(const sa_shape* shape, int granularity, const void* q, const void* k, const void* v,
+                      const int32_t* col_idx, const int32_t* col_cnt,
+                      const int32_t* slash_idx, const int32_t* slash_cnt,
+                      int32_t local_window,
+                      void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                      void* workspace, size_t workspace_bytes, void* stream) {
   Dims d;
   sa_status s = check_shape(shape, &d);
   if (s != SA_OK) return s;
+  const bool blocks = granularity != 1;
+  if (blocks) {
+    s = check_granularity(granularity);
+    if (s != SA_OK) return s;
+  }
   if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || col_idx == nullptr ||
       col_cnt == nullptr || slash_idx == nullptr || slash_cnt == nullptr)
     return SA_ERR_INVALID_ARG;
   if (local_window < 1) return SA_ERR_INVALID_ARG;
   if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
-  SparseWs w = sparse_ws(d);
-  s = check_ws(workspace, workspace_bytes, w.total);
+  const BlockWs bw = block_ws(d, blocks ? granularity : 64);
+  const SparseWs& w = bw.sp;
+  s = check_ws(workspace, workspace_bytes, blocks ? bw.total : w.total);
   if (s != SA_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
@@ -259,16 +357,33 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
   sa::MaskPrepParams M;
   {
     Scope sc(SA_K_MASK_PREP, st);
-    // merge_index, slash side: bitmaps of kept columns / offsets and touched tile diagonals
     memset(&M, 0, sizeof(M));
-    M.col_idx = col_idx; M.col_cnt = col_cnt; M.slash_idx = slash_idx; M.slash_cnt = slash_cnt;
     M.col_bits = reinterpret_cast<uint32_t*>(ws + w.cbits);
     M.off_bits = reinterpret_cast<uint32_t*>(ws + w.obits);
     M.dlist = reinterpret_cast<int32_t*>(ws + w.dlist);
     M.dcnt = reinterpret_cast<int32_t*>(ws + w.dcnt);
-    M.n_bh = d.n_bh; M.S = d.S; M.window = local_window;
-    M.cb_words = w.cb_words; M.rb_words = w.rb_words; M.dlist_stride = w.dlist_stride; M.off_max = w.off_max;
-    s = dev(sa::launch_mask_prep(M, st));
+    if (!blocks) {
+      // merge_index, slash side: bitmaps of kept columns / offsets and touched tile diagonals
+      M.col_idx = col_idx; M.col_cnt = col_cnt; M.slash_idx = slash_idx; M.slash_cnt = slash_cnt;
+      M.n_bh = d.n_bh; M.S = d.S; M.window = local_window;
+      M.cb_words = w.cb_words; M.rb_words = w.rb_words; M.dlist_stride = w.dlist_stride; M.off_max = w.off_max;
+      s = dev(sa::launch_mask_prep(M, st));
+    } else {
+      // the same metadata from block lists; from here on the selected key blocks are
+      // the token columns they hold
+      sa::BlockPrepParams B;
+      memset(&B, 0, sizeof(B));
+      B.col_blk = col_idx; B.col_bcnt = col_cnt; B.slash_blk = slash_idx; B.slash_bcnt = slash_cnt;
+      B.tok_idx = reinterpret_cast<int32_t*>(ws + bw.tok_idx);
+      B.tok_cnt = reinterpret_cast<int32_t*>(ws + bw.tok_cnt);
+      B.diag_bits = reinterpret_cast<uint32_t*>(ws + bw.dbits);
+      B.col_bits = M.col_bits; B.off_bits = M.off_bits; B.dlist = M.dlist; B.dcnt = M.dcnt;
+      B.n_bh = d.n_bh; B.S = d.S; B.window = local_window;
+      B.cb_words = w.cb_words; B.rb_words = w.rb_words; B.dlist_stride = w.dlist_stride; B.off_max = w.off_max;
+      B.blk = granularity; B.nb = bw.nb; B.db_words = bw.db_words;
+      s = dev(sa::launch_block_prep(B, st));
+      col_idx = B.tok_idx; col_cnt = B.tok_cnt;
+    }
     if (s != SA_OK) return s;
 
     // V^T for the contiguous (slash / window) tiles
@@ -312,6 +427,32 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
   P.dlist_stride = w.dlist_stride; P.off_max = w.off_max;
   Scope sc(SA_K_SPARSE_FLASH, st);
   return dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
+}
+}  // namespace
+
+extern "C" {
+
+sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
+                         const int32_t* col_idx, const int32_t* col_cnt,
+                         const int32_t* slash_idx, const int32_t* slash_cnt,
+                         int32_t local_window,
+                         void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  return sparse_attn(shape, 1, q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window, out, out_dtype,
+                     out_lse, tiles, workspace, workspace_bytes, stream);
+}
+
+sa_status sa_block_sparse_attn(const sa_shape* shape, int32_t granularity,
+                               const void* q, const void* k, const void* v,
+                               const int32_t* col_blocks, const int32_t* col_cnt,
+                               const int32_t* slash_blocks, const int32_t* slash_cnt,
+                               int32_t local_window,
+                               void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  if (granularity < 1) return SA_ERR_INVALID_ARG;
+  if (granularity == 1) return SA_ERR_UNSUPPORTED;   // per-token strips are sa_sparse_attn
+  return sparse_attn(shape, granularity, q, k, v, col_blocks, col_cnt, slash_blocks, slash_cnt, local_window, out,
+                     out_dtype, out_lse, tiles, workspace, workspace_bytes, stream);
 }
 
 sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
@@ -377,6 +518,6 @@ const char* sa_status_string(int status) {
   }
 }
 
-int sa_version(void) { return 100; }
+int sa_version(void) { return 110; }
 
 }  // extern "C"

@@ -60,6 +60,21 @@ struct MaskPrepParams {
 hipError_t launch_mask_prep(const MaskPrepParams& P, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t st);
 
+// block granularity: lists of selected key blocks / offset blocks of blk tokens
+struct BlockPrepParams {
+  const int32_t* col_blk; const int32_t* col_bcnt;     // [n_bh, nb], [n_bh]
+  const int32_t* slash_blk; const int32_t* slash_bcnt;
+  int32_t* tok_idx; int32_t* tok_cnt;                  // [n_bh, S], [n_bh]: the key blocks as token columns
+  uint32_t* diag_bits;                                 // [n_bh, db_words]: kept block diagonals
+  uint32_t* col_bits; uint32_t* off_bits;
+  int32_t* dlist; int32_t* dcnt;
+  int n_bh, S, window, cb_words, rb_words, dlist_stride, off_max;
+  int blk, nb, db_words;
+};
+hipError_t launch_block_prep(const BlockPrepParams& P, hipStream_t st);
+// out[r][b] = sum of in[r][b*blk .. (b+1)*blk), r < n_rows, rows of S floats
+hipError_t launch_block_reduce(const float* in, float* out, int n_rows, int S, int blk, hipStream_t st);
+
 struct ScoreParams {
   const uint16_t* q; const uint16_t* k;
   const float* lse;         // [n_bh, n_s] natural log

@@ -112,7 +112,9 @@ def test_sampling_validation(lib, B):
     assert call(B._CSampling(1024, 1, 1)) == SA_INVALID                     # more rows than the sequence
     assert call(B._CSampling(50, 1, 1)) == SA_INVALID                       # not a multiple of 32
     assert call(B._CSampling(64, 2, 1)) == SA_UNSUPPORTED                   # chunk_n > 1 not built yet
-    assert call(B._CSampling(64, 1, 128)) == SA_UNSUPPORTED                 # block granularity not built yet
+    assert call(B._CSampling(64, 1, 100)) == SA_UNSUPPORTED                 # block sizes: 64, 128, 256
+    assert call(B._CSampling(64, 1, 0)) == SA_INVALID
+    assert call(B._CSampling(64, 1, 128)) == SA_WORKSPACE                   # valid; 16 bytes is too small
     assert call(B._CSampling(64, 1, 1), col=None) == SA_INVALID
     assert call(B._CSampling(64, 1, 1)) == SA_WORKSPACE                     # 16 bytes is too small
 
@@ -135,6 +137,43 @@ def test_select_and_sparse_validation(lib, B):
     assert sparse(0) == SA_INVALID                                           # every row must keep its diagonal
     assert sparse(4, cnt=None) == SA_INVALID
     assert sparse(4) == SA_WORKSPACE
+
+
+def test_block_entry_points_validation(lib, B):
+    sh = _shape(B)
+    assert lib.sa_block_scores(ctypes.byref(sh), 128, FAKE, FAKE, FAKE, None, None) == SA_INVALID
+    assert lib.sa_block_scores(ctypes.byref(sh), 0, FAKE, FAKE, FAKE, FAKE, None) == SA_INVALID
+    assert lib.sa_block_scores(ctypes.byref(sh), 96, FAKE, FAKE, FAKE, FAKE, None) == SA_UNSUPPORTED
+
+    def sel(g, ac=0.5):
+        return lib.sa_select_blocks(ctypes.byref(sh), g, FAKE, FAKE, ctypes.c_float(ac), ctypes.c_float(0.5),
+                                    FAKE, FAKE, FAKE, FAKE, None, 0, None)
+
+    assert sel(0) == SA_INVALID
+    assert sel(1) == SA_UNSUPPORTED                                          # per-token: sa_select_strips
+    assert sel(32) == SA_UNSUPPORTED
+    assert sel(128, ac=-1.0) == SA_INVALID
+
+    def attn(g, window=4, ws_bytes=16, cnt=FAKE):
+        return lib.sa_block_sparse_attn(ctypes.byref(sh), g, FAKE, FAKE, FAKE, FAKE, cnt, FAKE, FAKE, window,
+                                        FAKE, 0, None, None, FAKE, ws_bytes, None)
+
+    assert attn(-1) == SA_INVALID
+    assert attn(1) == SA_UNSUPPORTED
+    assert attn(512) == SA_UNSUPPORTED
+    assert attn(128, window=0) == SA_INVALID
+    assert attn(128, cnt=None) == SA_INVALID
+    assert attn(128) == SA_WORKSPACE
+    # the block path needs the strip path's workspace and a little more
+    sm = B._CSampling(0, 1, 128)
+    nb = lib.sa_workspace_bytes(4, ctypes.byref(sh), ctypes.byref(sm))
+    assert nb > lib.sa_workspace_bytes(2, ctypes.byref(sh), None) and nb % 256 == 0
+    assert lib.sa_workspace_bytes(4, ctypes.byref(sh), None) == 0
+    assert lib.sa_workspace_bytes(4, ctypes.byref(sh), ctypes.byref(B._CSampling(0, 1, 100))) == 0
+    # sampling at block granularity needs room for the per-token scores as well
+    s1 = lib.sa_workspace_bytes(0, ctypes.byref(sh), ctypes.byref(B._CSampling(64, 1, 1)))
+    s128 = lib.sa_workspace_bytes(0, ctypes.byref(sh), ctypes.byref(B._CSampling(64, 1, 128)))
+    assert s128 >= s1 + 2 * 4 * 512 * 4
 
 
 def test_profile_read_before_enable(lib):
