@@ -81,6 +81,28 @@ def touched_block_fraction(S: int, cols: np.ndarray, offs: np.ndarray, window: i
     return touched / (nb * (nb + 1) / 2.0)
 
 
+def block_mask_density(S: int, col_blocks: np.ndarray, slash_blocks: np.ndarray, window: int, blk: int) -> float:
+    """Kept fraction of the blk x blk blocks of the causal triangle under the block
+    mask (Algorithm 1 at block granularity): block (I, J), J <= I, is kept when J is a
+    selected key block or I - J is a kept block diagonal - b and b + 1 for a selected
+    offset block b, and the diagonals the local window reaches."""
+    nb = (S + blk - 1) // blk
+    diag = np.zeros(nb + 1, dtype=bool)
+    diag[np.asarray(slash_blocks, dtype=np.int64)] = True
+    diag[np.asarray(slash_blocks, dtype=np.int64) + 1] = True
+    diag[: (window + blk - 2) // blk + 1] = True
+    diag = diag[:nb]
+    colk = np.zeros(nb, dtype=bool)
+    colk[np.asarray(col_blocks, dtype=np.int64)] = True
+    # diagonal delta holds nb - delta blocks; a kept column J holds nb - J blocks (rows I >= J)
+    n_diag = int(np.sum(nb - np.nonzero(diag)[0]))
+    n_col = int(np.sum(nb - np.nonzero(colk)[0]))
+    # counted twice: kept column J on kept diagonal delta with J + delta <= nb - 1
+    dd = np.nonzero(diag)[0]
+    both = int(np.sum(np.searchsorted(dd, nb - 1 - np.nonzero(colk)[0], side="right")))
+    return (n_diag + n_col - both) / (nb * (nb + 1) / 2.0)
+
+
 def cpu_baseline(wl, x, alpha: float, budget_s: float) -> dict:
     """Oracle timing on a bounded sample (about 2 x budget_s of CPU work), scaled
     linearly to ms per layer.  The oracle runs as it stands: numpy fp64 on the
@@ -138,6 +160,7 @@ def main() -> int:
     ap.add_argument("--dense-iters", type=int, default=2)
     ap.add_argument("--no-sweep", action="store_true", help="skip the alpha sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-block", action="store_true", help="skip the block-granularity runs")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates HBM byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=8.0,
@@ -263,6 +286,37 @@ def main() -> int:
                 "flash_tflops": float(tl.sum()) * TILE_FLOP / (t_fl * 1e-3) / 1e12,
             })
             log(f"alpha {a}: {json.dumps(sweep[-1])}")
+    # ---- the same workload at block granularity (Algorithm 1 with blk = 128): with the
+    #      workload's sampled rows, and with the paper's 128 sampled rows -----------------
+    block_runs = []
+    if not args.no_block:
+        blk = 128
+        for bn_s in sorted({n_s, min(128, S)}, reverse=True):
+            bplan = sa.SampleAttentionPlan(shape, bn_s, granularity=blk)
+            for a in wl.alphas:
+                bplan.run(q, k, v, a, a, w)          # warm
+                torch.cuda.synchronize()
+                sa.sa_profile_enable(True)
+                bplan.run(q, k, v, a, a, w)
+                torch.cuda.synchronize()
+                t = {n: float(np.mean(sa.sa_profile_read(n))) for n in
+                     ("row_lse", "score_accum", "score_final", "select", "mask_prep", "sparse_flash")}
+                tl = bplan.tiles.cpu().numpy().astype(np.int64)
+                cca, sca = bplan.col_cnt.cpu().numpy(), bplan.slash_cnt.cpu().numpy()
+                total = sum(t.values())
+                block_runs.append({
+                    "granularity": blk, "n_sample_rows": bn_s, "alpha": a, "ms_layer": total,
+                    "sparse_flash_ms": t["sparse_flash"],
+                    "computed_tile_fraction": float(tl.sum()) / dense_tiles,
+                    "block_mask_density_head0": block_mask_density(
+                        S, bplan.col_idx[0, :int(cca[0])].cpu().numpy(),
+                        bplan.slash_idx[0, :int(sca[0])].cpu().numpy(), w, blk),
+                    "mean_k_c_blocks": float(cca.mean()), "mean_k_s_blocks": float(sca.mean()),
+                    "speedup_vs_dense": (dense_ms / total) if dense_ms else None,
+                    "flash_tflops": float(tl.sum()) * TILE_FLOP / (t["sparse_flash"] * 1e-3) / 1e12,
+                })
+                log(f"block: {json.dumps(block_runs[-1])}")
+            del bplan
     sa.sa_profile_enable(False)
 
     cpu = None
@@ -315,6 +369,7 @@ def main() -> int:
         "dense_kernel_tflops": dense_kernel_tflops if dense_ms else None,
         "speedup_vs_dense": (dense_ms / ms_per_step) if dense_ms else None,
         "alpha_sweep": sweep,
+        "block_granularity_runs": block_runs,
     }
     print(json.dumps(line), flush=True)
     return 0

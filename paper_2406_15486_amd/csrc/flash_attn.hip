@@ -477,6 +477,9 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
         uint32_t cw = mw[16 + sb] >> (8 * hf);                     // bit 16u+e <-> key is a selected column
         km[sb] = ow & ~cw;
       }
+      // a tile that keeps every pair (a whole block of the block mask, the inside of a
+      // band of offsets) needs no masking at all
+      masked = __builtin_amdgcn_ballot_w64((km[0] & km[1]) != 0xFFFFFFFFu) != 0ull;
     }
     if (masked) {
 #pragma unroll

@@ -28,3 +28,23 @@ def test_counts_match_brute_force(S, seed):
     touched = sum(M[bi * blk:(bi + 1) * blk, bj * blk:(bj + 1) * blk].any()
                   for bi in range(nb) for bj in range(bi + 1))
     assert bench.touched_block_fraction(S, cols, offs, w) == pytest.approx(touched / (nb * (nb + 1) / 2.0), rel=1e-12)
+
+
+@pytest.mark.parametrize("S,blk,w,seed", [(1024, 128, 128, 1), (1000, 64, 1, 2), (700, 128, 300, 3), (256, 128, 5, 4)])
+def test_block_mask_density_matches_brute_force(S, blk, w, seed):
+    # block (I, J) is kept when J is selected, or a full block on diagonal I - J
+    # (offsets blk*(I-J) - (blk-1) .. blk*(I-J) + (blk-1)) holds a kept offset
+    rng = np.random.default_rng(seed)
+    nb = (S + blk - 1) // blk
+    Ic = np.sort(rng.choice(nb, rng.integers(0, nb // 2 + 1), replace=False))
+    Is = np.sort(rng.choice(nb, rng.integers(0, nb // 2 + 1), replace=False))
+    keep_off = np.zeros((nb + 2) * blk, dtype=bool)
+    for b in Is:
+        keep_off[b * blk:(b + 1) * blk] = True
+    keep_off[:w] = True
+    kept = 0
+    for bi in range(nb):
+        for bj in range(bi + 1):
+            lo, hi = max(blk * (bi - bj) - (blk - 1), 0), blk * (bi - bj) + blk - 1
+            kept += bool(bj in Ic or keep_off[lo:hi + 1].any())
+    assert bench.block_mask_density(S, Ic, Is, w, blk) == pytest.approx(kept / (nb * (nb + 1) / 2.0), rel=1e-12)

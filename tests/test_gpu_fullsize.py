@@ -103,3 +103,46 @@ def test_glm128k_benchmark_config():
     # the benchmark's workload; whole-head oracle scores would take minutes, so
     # stage 1 is checked through row log-sum-exps, invariants and reproducibility
     _run_full("glm128k", 0.95, score_heads=[], attn_heads=[5, 30], n_rows=40, lse_rows=24)
+
+
+def test_glm128k_block_granularity():
+    """The benchmark workload at the paper's granularity: blk = 128 and the last
+    128 rows sampled (Algorithm 1 with chunk_n = 1).  Whole-head oracle scores
+    are affordable here (128 sampled rows)."""
+    import paper_2406_15486_amd as sa
+    wl = CONFIGS["glm128k"]
+    S, Hq, Hkv, w = wl.seq_len, wl.n_q_heads, wl.n_kv_heads, wl.window
+    blk, n_s, alpha = 128, 128, 0.95
+    G = Hq // Hkv
+    nb = (S + blk - 1) // blk
+    _say(f"glm128k block: generating inputs S={S}")
+    x = make_inputs(wl)
+    q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    plan = sa.SampleAttentionPlan(sa.Shape(1, Hq, Hkv, S), n_s, granularity=blk)
+    out = plan.run(q, k, v, alpha, alpha, w)
+    torch.cuda.synchronize()
+    cb, sb = plan.col.cpu().numpy(), plan.slash.cpu().numpy()
+    cc, sc = plan.col_cnt.cpu().numpy(), plan.slash_cnt.cpu().numpy()
+    ci, si = plan.col_idx.cpu().numpy(), plan.slash_idx.cpu().numpy()
+    assert cb.shape == (Hq, nb)
+    assert np.all(np.abs(cb.astype(np.float64).sum(1) - n_s) < 2e-3 * n_s)
+    assert np.all(np.abs(sb.astype(np.float64).sum(1) - n_s) < 2e-3 * n_s)
+    a32 = float(np.float32(alpha))
+    for h in range(Hq):
+        assert np.array_equal(ci[h, :cc[h]], O.select(cb[h], a32)), ("col", h)
+        assert np.array_equal(si[h, :sc[h]], O.select(sb[h], a32)), ("slash", h)
+    _say(f"glm128k block: selection bit-exact on {Hq} heads; mean k_c {cc.mean():.0f} k_s {sc.mean():.0f} of {nb}")
+    for h in (3, 28):
+        _say(f"glm128k block: oracle stage 1, head {h}")
+        wc, ws, _ = O.sample_scores(_f64(x["q"][h]), _f64(x["k"][h // G]), n_s)
+        for got, want, nm in ((cb[h], O.block_reduce(wc, blk), "col"), (sb[h], O.block_reduce(ws, blk), "slash")):
+            worst = (np.abs(got - want) / (1e-4 * np.abs(want) + 1e-6)).max()
+            _say(f"   {nm} blocks: worst err/bound {worst:.3f}")
+            assert worst <= 1.0, (nm, h, worst)
+    rows = np.unique(np.concatenate([np.linspace(0, S - 1, 40).astype(np.int64), [0, 1, 127, 128, 255, 256, S - 1]]))
+    for h in (5, 30):
+        want, _ = O.block_masked_attn(_f64(x["q"][h]), _f64(x["k"][h // G]), _f64(x["v"][h // G]),
+                                      ci[h, :cc[h]], si[h, :sc[h]], w, blk, rows=rows)
+        err = np.abs(out[0, h].float().cpu().numpy()[rows] - want)
+        _say(f"glm128k block: out head {h}: max-abs {err.max():.3e} mean-abs {err.mean():.3e}")
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3
