@@ -113,7 +113,9 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   const uint32_t smem_lds = __builtin_amdgcn_readfirstlane((int)(uintptr_t)(__attribute__((address_space(3))) char*)smem);
 
   // ---- which (head, query tile) this workgroup owns ------------------------
-  int bh, a;
+  // (the log-sum-exp sweep may also cut the keys of a query tile into k_splits
+  // equal parts, one workgroup each, to even out the last round of the launch)
+  int bh, a, split = 0;
   {
     const int bid = blockIdx.x;
     if (MODE == 2) {
@@ -137,8 +139,11 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       int xcd = bid & 7, slot = bid >> 3;
       int bl = slot / P.group, hg = slot % P.group;
       int bundle = bl * 8 + xcd;
-      if (bundle >= P.n_qtiles * P.n_bkv) return;
-      a = P.n_qtiles - 1 - bundle / P.n_bkv;
+      const int ks = (MODE == 1) ? P.k_splits : 1;
+      if (bundle >= P.n_qtiles * ks * P.n_bkv) return;
+      const int av = P.n_qtiles * ks - 1 - bundle / P.n_bkv;
+      a = av / ks;
+      split = av % ks;
       int bkv = bundle % P.n_bkv;
       bh = bkv * P.group + hg;
     }
@@ -187,8 +192,14 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   }
   n_col_tiles = __builtin_amdgcn_readfirstlane(n_col_tiles);
   n_rng = __builtin_amdgcn_readfirstlane(n_rng);
-  const int n_tiles = __builtin_amdgcn_readfirstlane(
-      (MODE == 2) ? (n_col_tiles + n_rng) : (min(i_last_wg, S - 1) / BK + 1));
+  int t_base = 0;                        // first key tile of this workgroup's share of the causal sweep
+  int n_sweep = min(i_last_wg, S - 1) / BK + 1;
+  if (MODE == 1 && P.k_splits > 1) {
+    t_base = (int)((long long)n_sweep * split / P.k_splits);
+    n_sweep = (int)((long long)n_sweep * (split + 1) / P.k_splits) - t_base;
+  }
+  t_base = __builtin_amdgcn_readfirstlane(t_base);
+  const int n_tiles = __builtin_amdgcn_readfirstlane((MODE == 2) ? (n_col_tiles + n_rng) : n_sweep);
 
   // Descriptor of tile t.  A range tile is named by its tile diagonal d: key tile
   // a64 + 3 - d, which the 256 rows meet at offsets [64 d - 255, 64 d + 63].  The d
@@ -207,7 +218,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   // kind and first key of tile t (wave-uniform; no memory access)
   auto is_col = [&](int t) -> bool { return MODE == 2 && t < n_col_tiles; };
   auto first_key = [&](int t, int d) -> int {          // contiguous tiles only; d = list entry
-    return (MODE == 2) ? (a64 + 3 - (d & kDiagMask)) * BK : t * BK;
+    return (MODE == 2) ? (a64 + 3 - (d & kDiagMask)) * BK : (t + (MODE == 1 ? t_base : 0)) * BK;
   };
   // array bases as scalars, once
   const uint64_t s_kbase = scalar_ptr(kbase), s_vtbase = scalar_ptr(vtbase);
@@ -672,7 +683,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   if (MODE == 2 && P.tiles != nullptr && lane == 0 && tiles_done > 0) atomicAdd(P.tiles + bh, tiles_done);
   if (!row_ok) return;
   if (P.lse != nullptr && hf == 0) {
-    size_t at = (MODE == 1) ? ((size_t)bh * P.n_qrows + (i_me - P.q_row0)) : ((size_t)bh * S + i_me);
+    size_t at = (MODE == 1) ? (((size_t)split * P.n_bh + bh) * P.n_qrows + (i_me - P.q_row0)) : ((size_t)bh * S + i_me);
     P.lse[at] = m_run * kLn2 + __logf(l_tot);
   }
   if (WITH_V) {
@@ -696,6 +707,40 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   }
 }
 
+// out[i] = log sum_s exp(part[s][i]): the key splits of the log-sum-exp sweep, in fixed order
+__global__ void lse_combine_kernel(const float* part, float* out, size_t n, int k) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float m = part[i];
+  for (int s = 1; s < k; ++s) m = fmaxf(m, part[(size_t)s * n + i]);
+  float z = 0.f;
+  for (int s = 0; s < k; ++s) z += __expf(part[(size_t)s * n + i] - m);
+  out[i] = m + __logf(z);
+}
+
+hipError_t launch_lse_combine(const float* part, float* out, size_t n, int k, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(lse_combine_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part, out, n, k);
+  return hipGetLastError();
+}
+
+// How many key splits even out the log-sum-exp launch: W workgroups of equal length cut
+// k ways take ceil(W k / 256) / k rounds on 256 CUs; a split keeps at least 64 tiles, and
+// every row must see a key in every split (the sampled rows start at row S - n_s).
+int lse_key_splits(int S, int n_s, int n_bh) {
+  const int n_qtiles = (n_s + kFlashBQ - 1) / kFlashBQ;
+  const long long W = (long long)n_qtiles * n_bh;
+  const int min_tiles = (S - n_s) / kFlashBK;       // key tiles the first sampled row sees, at least
+  int best = 1;
+  double best_t = (double)((W + 255) / 256);
+  for (int k = 2; k <= 8; k *= 2) {
+    if (min_tiles / k < 64) break;
+    double t = (double)((W * k + 255) / 256) / k;
+    if (t < best_t - 1e-9) { best_t = t; best = k; }
+  }
+  return best;
+}
+
 template <int MODE, bool OUT_F32>
 static hipError_t launch_one(const FlashParams& P, int grid, hipStream_t st) {
   size_t shmem = LDS_B;
@@ -711,7 +756,7 @@ hipError_t launch_flash(int mode, bool out_f32, const FlashParams& P, hipStream_
   if (mode == 2) {
     grid = (P.n_bh >= 8) ? 8 * P.n_qtiles * ((P.n_bh + 7) / 8) : P.n_qtiles * P.n_bh;
   } else {
-    int bundles = P.n_qtiles * P.n_bkv;
+    int bundles = P.n_qtiles * (mode == 1 ? P.k_splits : 1) * P.n_bkv;
     grid = ((bundles + 7) / 8) * 8 * P.group;
   }
   if (grid <= 0) return hipSuccess;

@@ -60,11 +60,14 @@ sa_status check_ws(const void* ws, size_t have, size_t need) {
 }
 
 // ---- workspace layouts --------------------------------------------------------
-struct SampleWs { size_t lse, partial, tok_col, tok_slash, total; };
+struct SampleWs { size_t lse, lse_part, partial, tok_col, tok_slash, total; int k_splits; };
 SampleWs sample_ws(const Dims& d, int n_s, int granularity) {
   SampleWs w;
   size_t at = 0;
+  w.k_splits = sa::lse_key_splits(d.S, n_s, d.n_bh);
   w.lse = at;     at += align_up((size_t)d.n_bh * n_s * sizeof(float));
+  w.lse_part = at;
+  if (w.k_splits > 1) at += align_up((size_t)w.k_splits * d.n_bh * n_s * sizeof(float));
   w.partial = at; at += align_up(sa::score_partial_floats(d.S, n_s, d.n_bh) * sizeof(float));
   w.tok_col = w.tok_slash = at;
   if (granularity > 1) {   // per-token scores, reduced to blocks afterwards
@@ -149,6 +152,7 @@ sa::FlashParams base_flash(const Dims& d, const void* q, const void* k) {
   P.scale_log2 = d.scale * 1.4426950408889634f;
   P.n_qtiles = (d.S + sa::kFlashBQ - 1) / sa::kFlashBQ;
   P.q_row0 = 0; P.n_qrows = d.S;
+  P.k_splits = 1;
   return P;
 }
 
@@ -214,13 +218,16 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
 
   // pass 1: log-sum-exp of every sampled row (flash sweep without V)
   sa::FlashParams P = base_flash(d, q, k);
-  P.lse = lse;
+  P.k_splits = w.k_splits;
+  P.lse = w.k_splits > 1 ? reinterpret_cast<float*>(ws + w.lse_part) : lse;
   P.q_row0 = d.S - n_s;
   P.n_qrows = n_s;
   P.n_qtiles = (n_s + sa::kFlashBQ - 1) / sa::kFlashBQ;
   {
     Scope sc(SA_K_ROW_LSE, st);
     s = dev(sa::launch_flash(1, false, P, st));
+    if (s == SA_OK && w.k_splits > 1)
+      s = dev(sa::launch_lse_combine(P.lse, lse, (size_t)d.n_bh * n_s, w.k_splits, st));
   }
   if (s != SA_OK) return s;
 

@@ -20,6 +20,8 @@ struct FlashParams {
   float scale_log2;         // softmax scale * log2(e)
   int n_qtiles;             // 256-row query tiles to process
   int q_row0, n_qrows;      // first query row and number of rows (sampled rows in mode 1)
+  int k_splits;             // mode 1: the keys of a query tile are cut into this many workgroups (>= 1);
+                            // lse is then [k_splits, n_bh, n_qrows] partial values (launch_lse_combine)
   // strip-masked mode only
   const uint16_t* kc;           // [n_bh, S_pad, 128] K rows gathered by column index
   const uint16_t* vct;          // [n_bh, 128, S_pad] V rows gathered and transposed
@@ -35,6 +37,8 @@ struct FlashParams {
 
 // mode 0: dense causal; 1: row log-sum-exp of rows [q_row0, q_row0+n_qrows); 2: strip mask
 hipError_t launch_flash(int mode, bool out_f32, const FlashParams& P, hipStream_t st);
+int lse_key_splits(int S, int n_s, int n_bh);
+hipError_t launch_lse_combine(const float* part, float* out, size_t n, int k, hipStream_t st);
 
 // out[g][d][c] = src[kv(g)][idx ? idx[g][c] : c][d] for c < cnt (zero beyond, up to C_pad);
 // optionally also rows_out[g][c][:] = src[kv(g)][idx[g][c]][:]
