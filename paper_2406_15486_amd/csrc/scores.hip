@@ -8,9 +8,12 @@
 // sum is in-lane arithmetic.  For the diagonals, the tile (row block b, key
 // sub-block kb) has exactly the lane/register -> diagonal mapping of every other
 // tile with the same b - kb, so tiles of one diagonal class are first added up
-// in registers; a finished class is added into a window in LDS that is private
-// to the wave and to the lane half (plain read-add-write: no two lanes of one
-// instruction share a slot, and a wave's LDS operations execute in order).
+// in registers.  A finished class (16 registers x 32 lanes per lane half, 59
+// distinct diagonals) is first summed along its diagonals across lanes - register
+// r is pulled from the lane e(r) positions on (one ds_bpermute each, all 16 in
+// flight together), which leaves every lane with the totals of two diagonals - and
+// then added into a window in LDS that is private to the wave and to the lane half
+// with two read-add-writes per lane whose slots no other lane touches.
 // The eight windows are combined in a fixed order into one partial per (key
 // block, chunk) and a second kernel adds the partials in a fixed order.  No
 // float atomics anywhere: repeated runs give identical bits.
@@ -104,7 +107,39 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
   for (int r = 0; r < 16; ++r) { dacc[0][r] = 0.f; dacc[1][r] = 0.f; }
   // slot of (row rb + m, key jw + 32 sb + ql) in this wave's window:
   //   32 (b - sb + 1) + (m - ql) + 31
-  float* mywin = win + (wave * 2 + hf) * WWIN + 31 - ql + 4 * hf;
+  // The class sum.  Register r of lane ql holds the diagonal e(r) - ql, with e(r) =
+  // 8 (r / 4) + r % 4, of 59 in all (-31 .. 27).  Lane L collects diagonal L - 31 (from
+  // the registers with e(r) <= L, lane e(r) + 31 - L) and diagonal L + 1 (from the
+  // others, lane e(r) - 1 - L): for each r one pull from lane (e(r) + 31 - L) mod 32 of
+  // its own half, credited to the one or the other by 0/1 factors (the products are
+  // exact).  Their window slots are 32 b' + L and 32 b' + 32 + L.
+  float* mywin = win + (wave * 2 + hf) * WWIN + ql + 4 * hf;
+  int pull[16];
+  float first[16], second[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int e = 8 * (r >> 2) + (r & 3);
+    pull[r] = 4 * (((e + 31 - ql) & 31) + 32 * hf);
+    first[r] = (ql >= e) ? 1.f : 0.f;
+    second[r] = 1.f - first[r];
+  }
+  // add class C (held in dacc[C]) into the window at block position bpos, and clear it
+  auto flush_class = [&](f32x16& acc, int bpos) {
+    float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float v = __int_as_float(__builtin_amdgcn_ds_bpermute(pull[r], __float_as_int(acc[r])));
+      a1 = fmaf(v, first[r], a1);
+      a2 = fmaf(v, second[r], a2);
+      acc[r] = 0.f;
+    }
+    volatile lds_f32* s1 = (volatile lds_f32*)(mywin + 32 * bpos);
+    *s1 = *s1 + a1;
+    if (ql < 27) {                                   // diagonals 28 .. 32 do not exist
+      volatile lds_f32* s2 = (volatile lds_f32*)(mywin + 32 * bpos + 32);
+      *s2 = *s2 + a2;
+    }
+  };
 
   // one 32-row block against both key sub-blocks; PAR = parity of b (compile time)
   auto do_block = [&](int b, auto par_tag) {
@@ -123,47 +158,47 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
         float4 l4 = *reinterpret_cast<const float4*>(ls + 8 * g + 4 * hf);
         lv[4 * g] = l4.x; lv[4 * g + 1] = l4.y; lv[4 * g + 2] = l4.z; lv[4 * g + 3] = l4.w;
       }
+      // both sub-blocks' products first (alternating accumulators), then their
+      // exponentials and sums: the matrix pipe works through the second product while
+      // the vector pipe starts on the first.  A sub-block that no row of the block
+      // reaches yet is computed all the same and masked to zero by the edge path.
+      f32x16 s2[2];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s2[0][r] = 0.f; s2[1][r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        s2[0] = mfma_32x32x16(qf[ks], kf[0][ks], s2[0]);
+        s2[1] = mfma_32x32x16(qf[ks], kf[1][ks], s2[1]);
+      }
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
         const int jsb = jw + 32 * sb;
-        if (rb + 31 >= jsb) {
-          f32x16 s;
+        // element r: query row rb + 8*(r/4) + 4*hf + r%4, key jsb + ql
+        const bool edge = (rb < jsb + 32) || (rb + 32 > S);
+        const int j_me = jsb + ql;
+        // straight-line code: all exponentials first, the (rare) edge mask in one
+        // wave-uniform branch, then the sums
+        float p[16];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-          for (int ks = 0; ks < 8; ++ks) s = mfma_32x32x16(qf[ks], kf[sb][ks], s);
-          // element r: query row rb + 8*(r/4) + 4*hf + r%4, key jsb + ql
-          const bool edge = (rb < jsb + 32) || (rb + 32 > S);
-          const int j_me = jsb + ql;
-          float csum = 0.f;
+        for (int r = 0; r < 16; ++r) p[r] = fast_exp2(fmaf(s2[sb][r], c2, -lv[r]));
+        if (edge) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float p = fast_exp2(fmaf(s[r], c2, -lv[r]));
-            if (edge) {
-              int i = rb + 8 * (r >> 2) + 4 * hf + (r & 3);
-              p = (i >= j_me && i < S) ? p : 0.f;
-            }
-            csum += p;
-            dacc[(PAR + sb) & 1][r] += p;
+            int i = rb + 8 * (r >> 2) + 4 * hf + (r & 3);
+            p[r] = (i >= j_me && i < S) ? p[r] : 0.f;
           }
-          colacc[sb] += csum;
         }
+        float csum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          csum += p[r];
+          dacc[(PAR + sb) & 1][r] += p[r];
+        }
+        colacc[sb] += csum;
       }
     }
     // class b - 1 (tiles (b-1, 0) and (b, 1)) is complete: add it into the window
-    {
-      constexpr int C = (PAR + 1) & 1;
-      float* wp = mywin + 32 * b;              // 32 * ((b - 1) + 1)
-      // One register at a time: two registers of different lanes can name the
-      // same slot, so every read-add-write must finish (LDS executes a wave's
-      // operations in order) before the next register's starts.
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        volatile lds_f32* slot = (volatile lds_f32*)(wp + 8 * (r >> 2) + (r & 3));
-        *slot = *slot + dacc[C][r];
-        dacc[C][r] = 0.f;
-      }
-    }
+    flush_class(dacc[(PAR + 1) & 1], b);       // window position 32 * ((b - 1) + 1)
   };
 
   for (int b = b_first; b < nblk; b += 2) {
@@ -180,17 +215,7 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
     __syncthreads();
   }
   // the last class (only its sub-block-0 tile exists): b = nblk - 1
-  {
-    const int bl = nblk;                      // class nblk - 1 -> slot base 32 * nblk
-    float* wp = mywin + 32 * bl;
-    const int C = (nblk - 1) & 1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float add = (C == 0) ? dacc[0][r] : dacc[1][r];
-      volatile lds_f32* slot = (volatile lds_f32*)(wp + 8 * (r >> 2) + (r & 3));
-      *slot = *slot + add;
-    }
-  }
+  if (((nblk - 1) & 1) == 0) flush_class(dacc[0], nblk); else flush_class(dacc[1], nblk);
   __syncthreads();
 
   // column sums of this chunk (both lane halves hold disjoint rows)
