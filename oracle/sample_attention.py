@@ -30,6 +30,15 @@ What follows the paper, and where:
 * ``mask_diagnostics``- Sec. 3.3 (CRA = minimum kept probability mass over
                         queries) and Sec. 2.3 (sparsity ratio).
 
+* ``chunk_segments``, ``sample_scores_chunked``, ``chunked_masked_attn``,
+  ``chunked_sample_attention`` - chunk_n > 1 (Alg. 1 stage 1 ``Q_slice``,
+                        Sec. 4.2 "Query-Guided Chunked Sampling"): the queries are
+                        cut into chunk_n equal segments, the rows at the bottom of
+                        each segment are sampled, and what is selected from a
+                        chunk's scores masks the rows of that chunk's segment
+                        (``merge_index(I_c, I_s, itv)``; Fig. 6 caption: one set of
+                        strips "for each sampling region").
+
 Readings where the paper is silent (all listed again in the design notes):
 sort is descending; alpha is a fraction of the direction's total sampled mass;
 the cut uses ">="; alpha = 0 keeps nothing, alpha >= 1 keeps everything; ties
@@ -43,6 +52,10 @@ mask keeps every blk x blk block (by block row and block column) that holds at
 least one pair (i, j) of a selected key block, of such a band, or of the local
 window, decided from the block indices alone (so the mask of a block depends
 only on its block column and on block row minus block column).
+
+With chunk_n > 1: itv = S // chunk_n, segment m holds the rows [m itv, (m+1) itv)
+(the last one up to S), its sampled rows are the last n_s rows of the segment, and
+their softmax is causal as everywhere (keys j <= i).
 
 Pins (tests/test_oracle_*.py): fp64 ``scaled_dot_product_attention`` on CPU for
 dense and banded cases, pure-Python brute force from the definitions on small
@@ -325,6 +338,76 @@ def block_mask_density(S: int, col_blocks, slash_blocks, window: int, blk: int) 
         t = np.arange(a + 1)
         kept += int(np.sum(col_keep[t] | diag_keep[a - t]))
     return kept / (nb * (nb + 1) / 2.0)
+
+
+# ----------------------------------------------------------------------------
+# chunk_n > 1 (Alg. 1 stage 1: itv = S_q / chunk_n, Q_slice)
+# ----------------------------------------------------------------------------
+def chunk_segments(S: int, n_chunks: int):
+    """[(first row, one past the last row)] of the chunk_n query segments."""
+    if not (1 <= n_chunks <= S):
+        raise ValueError("n_chunks must be in [1, S]")
+    itv = S // n_chunks
+    return [(m * itv, (m + 1) * itv if m + 1 < n_chunks else S) for m in range(n_chunks)]
+
+
+def sample_scores_chunked(q, k, n_sample_rows: int, n_chunks: int, scale: Optional[float] = None):
+    """Per chunk: column and slash scores of the last ``n_sample_rows`` rows of
+    the chunk's segment.  Returns (col [chunk_n, S], slash [chunk_n, S])."""
+    q, k = _f64(q), _f64(k)
+    S, d = k.shape
+    sc = _scale(d, scale)
+    cols, slashes = [], []
+    for lo, hi in chunk_segments(S, n_chunks):
+        if not (1 <= n_sample_rows <= hi - lo):
+            raise ValueError("n_sample_rows must fit in a segment")
+        col = np.zeros(S)
+        slash = np.zeros(S)
+        for r in _chunks(np.arange(hi - n_sample_rows, hi, dtype=np.int64), S):
+            p, _ = _causal_softmax_rows(q, k, r, sc)
+            col += p.sum(axis=0)
+            for n, i in enumerate(r):
+                slash[: i + 1] += p[n, i::-1]
+        cols.append(col)
+        slashes.append(slash)
+    return np.stack(cols), np.stack(slashes)
+
+
+def chunked_masked_attn(q, k, v, col_idx, slash_idx, window: int, n_chunks: int,
+                        scale: Optional[float] = None, rows=None, blk: int = 1):
+    """Eq. 3 where the rows of segment m are masked by the strips (or, with
+    blk > 1, the blocks) selected from chunk m: ``col_idx[m]``, ``slash_idx[m]``.
+    Returns (O [n_rows, d], lse [n_rows])."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    S = k.shape[0]
+    rows = np.arange(q.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
+    out = np.empty((len(rows), v.shape[1]))
+    lse = np.empty(len(rows))
+    for m, (lo, hi) in enumerate(chunk_segments(S, n_chunks)):
+        sel = np.flatnonzero((rows >= lo) & (rows < hi))
+        if len(sel) == 0:
+            continue
+        if blk == 1:
+            o, l = masked_attn(q, k, v, col_idx[m], slash_idx[m], window, scale, rows[sel])
+        else:
+            o, l = block_masked_attn(q, k, v, col_idx[m], slash_idx[m], window, blk, scale, rows[sel])
+        out[sel] = o
+        lse[sel] = l
+    return out, lse
+
+
+def chunked_sample_attention(q, k, v, n_sample_rows: int, n_chunks: int, alpha_c: float, alpha_s: float,
+                             window: int, scale: Optional[float] = None, rows=None,
+                             blk: int = 1) -> Dict[str, object]:
+    """Alg. 1 end to end for one head with chunk_n >= 1 (and blk >= 1)."""
+    col, slash = sample_scores_chunked(q, k, n_sample_rows, n_chunks, scale)
+    if blk > 1:
+        col = np.stack([block_reduce(c, blk) for c in col])
+        slash = np.stack([block_reduce(s_, blk) for s_ in slash])
+    I_c = [select(c, alpha_c) for c in col]
+    I_s = [select(s_, alpha_s) for s_ in slash]
+    out, lse = chunked_masked_attn(q, k, v, I_c, I_s, window, n_chunks, scale, rows, blk)
+    return {"out": out, "lse": lse, "col": col, "slash": slash, "col_idx": I_c, "slash_idx": I_s}
 
 
 # ----------------------------------------------------------------------------
