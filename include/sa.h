@@ -14,7 +14,9 @@
  *
  * The same path at block granularity (Algorithm 1 "block_reduction", blk = 128
  * in the paper): sa_sample_scores with granularity > 1 (or sa_block_scores on
- * per-token scores), sa_select_blocks, sa_block_sparse_attn.
+ * per-token scores), sa_select_blocks, sa_block_sparse_attn.  With chunk_n > 1
+ * ("Query-Guided Chunked Sampling", Sec. 4.2): sa_sample_scores with n_chunks > 1,
+ * sa_select_chunked, sa_sparse_attn_chunked.
  *
  * Conventions shared by every entry point
  * ---------------------------------------
@@ -69,11 +71,14 @@ typedef struct {
 /* Stage-1 sampling.  n_sample_rows: the last n rows of the sequence are the
  * sampled queries (Algorithm 1 with chunk_n = 1), 1 <= n <= seq_len and a
  * multiple of 32 unless it equals seq_len.  n_chunks and granularity are the
- * paper's chunk_n and blk.  granularity 1 keeps scores per key / per offset;
+ * paper's chunk_n and blk.  With n_chunks = C > 1 the queries are cut into C
+ * segments of itv = seq_len / C rows and the last n rows of EACH segment are
+ * sampled (n <= itv, a multiple of 32); seq_len must then be a multiple of
+ * 256 * C (segments end at query-tile boundaries; SA_ERR_UNSUPPORTED
+ * otherwise).  granularity 1 keeps scores per key / per offset;
  * 64, 128 or 256 sums them over blocks of that many keys / offsets (multiples
  * of the kernels' 64-key tile that divide their 256-row query tile; the paper
- * uses 128).  This build implements n_chunks == 1 and these granularities
- * and returns SA_ERR_UNSUPPORTED otherwise. */
+ * uses 128); other values return SA_ERR_UNSUPPORTED. */
 typedef struct {
   int32_t n_sample_rows;
   int32_t n_chunks;
@@ -115,6 +120,10 @@ int32_t sa_rows_from_ratio(int32_t seq_len, float ratio);
  * n_blocks = ceil(seq_len / blk):
  *   col_scores[h, J]   = sum of the per-key scores of keys   [blk*J, blk*J + blk)
  *   slash_scores[h, b] = sum of the per-offset scores of offsets [blk*b, blk*b + blk)
+ * With sampling->n_chunks = C > 1 the outputs carry a leading chunk dimension,
+ * [C, batch*n_q_heads, n]: chunk m holds the scores of the rows
+ * [(m+1)*itv - n_sample_rows, (m+1)*itv), exactly as above (causal: those rows
+ * see keys up to their own position); row_lse must then be NULL.
  * The sums are formed in a fixed order: repeated calls give identical bits.
  */
 sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
@@ -183,6 +192,37 @@ sa_status sa_block_sparse_attn(const sa_shape* shape, int32_t granularity,
                                int32_t local_window,
                                void* out, int out_dtype, float* out_lse, uint64_t* tiles,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * chunk_n > 1 (Algorithm 1: itv, Q_slice, merge_index(I_c, I_s, itv); Sec. 4.2-4.3).
+ * sampling gives n_chunks = C and granularity (n_sample_rows is not read); all
+ * score, index and count arrays carry a leading chunk dimension:
+ * [C, batch*n_q_heads, n] and [C, batch*n_q_heads], n = seq_len candidates at
+ * granularity 1, ceil(seq_len / blk) at block granularity.
+ *
+ * sa_select_chunked: the selection of sa_select_strips / sa_select_blocks for
+ * every (chunk, head, direction) independently.
+ *
+ * sa_sparse_attn_chunked: what is selected from chunk m masks the query rows of
+ * segment m, [m*itv, (m+1)*itv): for those rows the mask is that of
+ * sa_sparse_attn (granularity 1) or sa_block_sparse_attn with chunk m's lists.
+ * Workspace: that of SA_OP_SPARSE_ATTN or SA_OP_BLOCK_SPARSE_ATTN.  `tiles`
+ * counts over all segments.
+ */
+sa_status sa_select_chunked(const sa_shape* shape, const sa_sampling* sampling,
+                            const float* col_scores, const float* slash_scores,
+                            float alpha_c, float alpha_s,
+                            int32_t* col_idx, int32_t* col_cnt,
+                            int32_t* slash_idx, int32_t* slash_cnt,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+sa_status sa_sparse_attn_chunked(const sa_shape* shape, const sa_sampling* sampling,
+                                 const void* q, const void* k, const void* v,
+                                 const int32_t* col_idx, const int32_t* col_cnt,
+                                 const int32_t* slash_idx, const int32_t* slash_cnt,
+                                 int32_t local_window,
+                                 void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Merge + attend (Algorithm 1 merge_index and sparse_flash_attn; Eq. 3 with

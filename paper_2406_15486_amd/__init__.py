@@ -14,11 +14,14 @@ from .binding import (  # noqa: F401
     Shape,
     lib_path,
     block_sample_attention,
+    chunked_sample_attention,
     load_library,
     n_blocks,
     sa_block_scores,
     sa_block_sparse_attn,
     sa_select_blocks,
+    sa_select_chunked,
+    sa_sparse_attn_chunked,
     sa_dense_attn,
     sa_profile_enable,
     sa_profile_read,

@@ -100,6 +100,14 @@ def load_library() -> ctypes.CDLL:
     lib.sa_block_sparse_attn.restype = ctypes.c_int
     lib.sa_block_sparse_attn.argtypes = [ctypes.POINTER(_CShape), ctypes.c_int32, vp, vp, vp, i32p, i32p, i32p, i32p,
                                          ctypes.c_int32, vp, ctypes.c_int, f32p, vp, vp, ctypes.c_size_t, vp]
+    lib.sa_select_chunked.restype = ctypes.c_int
+    lib.sa_select_chunked.argtypes = [ctypes.POINTER(_CShape), ctypes.POINTER(_CSampling), f32p, f32p,
+                                      ctypes.c_float, ctypes.c_float, i32p, i32p, i32p, i32p, vp,
+                                      ctypes.c_size_t, vp]
+    lib.sa_sparse_attn_chunked.restype = ctypes.c_int
+    lib.sa_sparse_attn_chunked.argtypes = [ctypes.POINTER(_CShape), ctypes.POINTER(_CSampling), vp, vp, vp,
+                                           i32p, i32p, i32p, i32p, ctypes.c_int32, vp, ctypes.c_int, f32p, vp,
+                                           vp, ctypes.c_size_t, vp]
     lib.sa_dense_attn.restype = ctypes.c_int
     lib.sa_dense_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p,
                                   vp, ctypes.c_size_t, vp]
@@ -158,18 +166,22 @@ def sa_rows_from_ratio(seq_len: int, ratio: float) -> int:
 
 # -------------------------------------------------------------- entry points --
 def sa_sample_scores(q, k, n_sample_rows: int, scale: float = 0.0, workspace=None, want_lse=False,
-                     granularity: int = 1):
+                     granularity: int = 1, n_chunks: int = 1):
     """Stage 1: column and slash scores of the last ``n_sample_rows`` queries.
     Returns (col [B*Hq, S] f32, slash [B*Hq, S] f32[, row_lse [B*Hq, n] f32]);
-    with granularity > 1 the two score tensors are [B*Hq, ceil(S / granularity)]."""
+    with granularity > 1 the two score tensors are [B*Hq, ceil(S / granularity)];
+    with n_chunks > 1 they carry a leading chunk dimension."""
     lib = load_library()
     sh = _shape_of(q, k, scale)
     _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
     _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
-    cs, sm = sh.c(), _CSampling(n_sample_rows, 1, granularity)
+    cs, sm = sh.c(), _CSampling(n_sample_rows, n_chunks, granularity)
     need = int(lib.sa_workspace_bytes(SA_OP_SAMPLE_SCORES, ctypes.byref(cs), ctypes.byref(sm)))
     ws = workspace if workspace is not None else _workspace(need, q.device)
-    col = torch.empty(sh.n_bh, n_blocks(sh.seq_len, max(granularity, 1)), dtype=torch.float32, device=q.device)
+    dims = (sh.n_bh, n_blocks(sh.seq_len, max(granularity, 1)))
+    if n_chunks != 1:
+        dims = (max(n_chunks, 1),) + dims
+    col = torch.empty(*dims, dtype=torch.float32, device=q.device)
     slash = torch.empty_like(col)
     lse = torch.empty(sh.n_bh, max(n_sample_rows, 1), dtype=torch.float32, device=q.device) if want_lse else None
     st = lib.sa_sample_scores(ctypes.byref(cs), ctypes.byref(sm), _ptr(q), _ptr(k), _ptr(col), _ptr(slash),
@@ -262,6 +274,59 @@ def sa_block_sparse_attn(q, k, v, col_blocks, col_cnt, slash_blocks, slash_cnt, 
                                   ws.numel() if ws is not None else 0, _stream())
     if st != 0:
         raise SaError(st, "sa_block_sparse_attn")
+    return out, lse, tiles
+
+
+def sa_select_chunked(col_scores, slash_scores, alpha_c: float, alpha_s: float, shape: Shape,
+                      n_chunks: int, granularity: int = 1):
+    """Stage 2 for every (chunk, head): inputs [C, B*Hq, n]; returns
+    (col_idx [C, B*Hq, n], col_cnt [C, B*Hq], slash_idx, slash_cnt)."""
+    lib = load_library()
+    n = n_blocks(shape.seq_len, max(granularity, 1))
+    _check(col_scores, torch.float32, (n_chunks, shape.n_bh, n), "col_scores")
+    _check(slash_scores, torch.float32, (n_chunks, shape.n_bh, n), "slash_scores")
+    dev = col_scores.device
+    col_idx = torch.empty(n_chunks, shape.n_bh, n, dtype=torch.int32, device=dev)
+    slash_idx = torch.empty_like(col_idx)
+    col_cnt = torch.empty(n_chunks, shape.n_bh, dtype=torch.int32, device=dev)
+    slash_cnt = torch.empty_like(col_cnt)
+    cs, sm = shape.c(), _CSampling(0, n_chunks, granularity)
+    st = lib.sa_select_chunked(ctypes.byref(cs), ctypes.byref(sm), _ptr(col_scores), _ptr(slash_scores),
+                               ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
+                               _ptr(col_idx), _ptr(col_cnt), _ptr(slash_idx), _ptr(slash_cnt), None, 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_select_chunked")
+    return col_idx, col_cnt, slash_idx, slash_cnt
+
+
+def sa_sparse_attn_chunked(q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window: int, n_chunks: int,
+                           granularity: int = 1, scale: float = 0.0, out_dtype: int = SA_OUT_BF16,
+                           workspace=None, want_lse: bool = False, want_tiles: bool = False):
+    """Attention where segment m of the queries is masked by chunk m's lists.
+    Returns (out, lse or None, tiles or None)."""
+    lib = load_library()
+    sh = _shape_of(q, k, scale)
+    _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
+    _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
+    _check(v, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "v")
+    n = n_blocks(sh.seq_len, max(granularity, 1))
+    for t, nm in ((col_idx, "col_idx"), (slash_idx, "slash_idx")):
+        _check(t, torch.int32, (n_chunks, sh.n_bh, n), nm)
+    for t, nm in ((col_cnt, "col_cnt"), (slash_cnt, "slash_cnt")):
+        _check(t, torch.int32, (n_chunks, sh.n_bh), nm)
+    cs, sm = sh.c(), _CSampling(0, n_chunks, granularity)
+    op = SA_OP_SPARSE_ATTN if granularity == 1 else SA_OP_BLOCK_SPARSE_ATTN
+    need = int(lib.sa_workspace_bytes(op, ctypes.byref(cs), ctypes.byref(sm)))
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    out = torch.empty(q.shape, dtype=torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16, device=q.device)
+    lse = torch.empty(sh.n_bh, sh.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
+    tiles = torch.empty(sh.n_bh, dtype=torch.int64, device=q.device) if want_tiles else None
+    st = lib.sa_sparse_attn_chunked(ctypes.byref(cs), ctypes.byref(sm), _ptr(q), _ptr(k), _ptr(v),
+                                    _ptr(col_idx), _ptr(col_cnt), _ptr(slash_idx), _ptr(slash_cnt),
+                                    int(local_window), _ptr(out), out_dtype, _ptr(lse), _ptr(tiles), _ptr(ws),
+                                    ws.numel() if ws is not None else 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_sparse_attn_chunked")
     return out, lse, tiles
 
 
@@ -425,4 +490,18 @@ def block_sample_attention(q, k, v, n_sample_rows: int, alpha_c: float, alpha_s:
     cb, sb = sa_sample_scores(q, k, n_sample_rows, scale, granularity=granularity)
     ci, cc, si, sc = sa_select_blocks(cb, sb, alpha_c, alpha_s, granularity, sh)
     out, _, _ = sa_block_sparse_attn(q, k, v, ci, cc, si, sc, local_window, granularity, scale, out_dtype)
+    return out
+
+
+def chunked_sample_attention(q, k, v, n_sample_rows: int, n_chunks: int, alpha_c: float, alpha_s: float,
+                             local_window: int, granularity: int = 1, scale: float = 0.0,
+                             out_dtype: int = SA_OUT_BF16):
+    """The whole path with chunk_n = n_chunks (Algorithm 1 as printed: the bottom
+    rows of every query segment are sampled, each segment gets its own mask)."""
+    sh = _shape_of(q, k, scale)
+    col, slash = sa_sample_scores(q, k, n_sample_rows, scale, granularity=granularity, n_chunks=n_chunks)
+    if n_chunks == 1:
+        col, slash = col[None], slash[None]
+    ci, cc, si, sc = sa_select_chunked(col, slash, alpha_c, alpha_s, sh, n_chunks, granularity)
+    out, _, _ = sa_sparse_attn_chunked(q, k, v, ci, cc, si, sc, local_window, n_chunks, granularity, scale, out_dtype)
     return out

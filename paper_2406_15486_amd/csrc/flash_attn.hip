@@ -133,6 +133,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
         bh = bid % P.n_bh;
         if (a < 0) return;
       }
+      a += P.qtile0;
     } else {
       // a bundle = the query heads sharing one KV head at one query tile; the
       // bundle's workgroups land on one XCD so the K/V stream is shared in L2.
@@ -726,11 +727,11 @@ hipError_t launch_lse_combine(const float* part, float* out, size_t n, int k, hi
 
 // How many key splits even out the log-sum-exp launch: W workgroups of equal length cut
 // k ways take ceil(W k / 256) / k rounds on 256 CUs; a split keeps at least 64 tiles, and
-// every row must see a key in every split (the sampled rows start at row S - n_s).
-int lse_key_splits(int S, int n_s, int n_bh) {
+// every row must see a key in every split (the sampled rows start at row_first).
+int lse_key_splits(int row_first, int n_s, int n_bh) {
   const int n_qtiles = (n_s + kFlashBQ - 1) / kFlashBQ;
   const long long W = (long long)n_qtiles * n_bh;
-  const int min_tiles = (S - n_s) / kFlashBK;       // key tiles the first sampled row sees, at least
+  const int min_tiles = row_first / kFlashBK;       // key tiles the first sampled row sees, at least
   int best = 1;
   double best_t = (double)((W + 255) / 256);
   for (int k = 2; k <= 8; k *= 2) {

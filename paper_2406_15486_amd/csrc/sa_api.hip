@@ -46,8 +46,13 @@ sa_status check_sampling(const sa_sampling* sm, const Dims& d) {
   if (sm == nullptr) return SA_ERR_INVALID_ARG;
   if (sm->n_sample_rows < 1 || sm->n_sample_rows > d.S) return SA_ERR_INVALID_ARG;
   if (sm->n_chunks < 1 || sm->granularity < 1) return SA_ERR_INVALID_ARG;
-  if (sm->n_chunks != 1) return SA_ERR_UNSUPPORTED;
   if (sm->granularity != 1 && check_granularity(sm->granularity) != SA_OK) return SA_ERR_UNSUPPORTED;
+  if (sm->n_chunks > 1) {
+    // segments of itv = S / chunk_n rows, cut at query-tile boundaries
+    if (d.S % (sm->n_chunks * sa::kFlashBQ) != 0) return SA_ERR_UNSUPPORTED;
+    if (sm->n_sample_rows > d.S / sm->n_chunks) return SA_ERR_INVALID_ARG;
+    if (sm->n_sample_rows % 32 != 0) return SA_ERR_INVALID_ARG;
+  }
   if (sm->n_sample_rows % 32 != 0 && sm->n_sample_rows != d.S) return SA_ERR_INVALID_ARG;
   return SA_OK;
 }
@@ -59,15 +64,22 @@ sa_status check_ws(const void* ws, size_t have, size_t need) {
   return SA_OK;
 }
 
+// chunk_n and blk of the calls that take no sampled-row count
+sa_status check_chunks(const Dims& d, int n_chunks, int granularity) {
+  if (n_chunks < 1 || granularity < 1) return SA_ERR_INVALID_ARG;
+  if (granularity != 1 && check_granularity(granularity) != SA_OK) return SA_ERR_UNSUPPORTED;
+  if (n_chunks > 1 && d.S % (n_chunks * sa::kFlashBQ) != 0) return SA_ERR_UNSUPPORTED;
+  return SA_OK;
+}
+
 // ---- workspace layouts --------------------------------------------------------
-struct SampleWs { size_t lse, lse_part, partial, tok_col, tok_slash, total; int k_splits; };
+constexpr int kMaxKeySplits = 8;
+struct SampleWs { size_t lse, lse_part, partial, tok_col, tok_slash, total; };
 SampleWs sample_ws(const Dims& d, int n_s, int granularity) {
   SampleWs w;
   size_t at = 0;
-  w.k_splits = sa::lse_key_splits(d.S, n_s, d.n_bh);
-  w.lse = at;     at += align_up((size_t)d.n_bh * n_s * sizeof(float));
-  w.lse_part = at;
-  if (w.k_splits > 1) at += align_up((size_t)w.k_splits * d.n_bh * n_s * sizeof(float));
+  w.lse = at;      at += align_up((size_t)d.n_bh * n_s * sizeof(float));
+  w.lse_part = at; at += align_up((size_t)kMaxKeySplits * d.n_bh * n_s * sizeof(float));
   w.partial = at; at += align_up(sa::score_partial_floats(d.S, n_s, d.n_bh) * sizeof(float));
   w.tok_col = w.tok_slash = at;
   if (granularity > 1) {   // per-token scores, reduced to blocks afterwards
@@ -207,52 +219,66 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   if (q == nullptr || k == nullptr || col_scores == nullptr || slash_scores == nullptr) return SA_ERR_INVALID_ARG;
   const int n_s = sampling->n_sample_rows;
   const int blk = sampling->granularity;
+  const int n_chunks = sampling->n_chunks;
   SampleWs w = sample_ws(d, n_s, blk);
   s = check_ws(workspace, workspace_bytes, w.total);
   if (s != SA_OK) return s;
+  if (row_lse != nullptr && n_chunks != 1) return SA_ERR_UNSUPPORTED;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
   float* lse = row_lse ? row_lse : reinterpret_cast<float*>(ws + w.lse);
-  float* tok_col = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_col) : col_scores;
-  float* tok_slash = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_slash) : slash_scores;
+  const size_t n_cand = (size_t)(d.S + blk - 1) / blk;       // scores per head and direction
 
-  // pass 1: log-sum-exp of every sampled row (flash sweep without V)
-  sa::FlashParams P = base_flash(d, q, k);
-  P.k_splits = w.k_splits;
-  P.lse = w.k_splits > 1 ? reinterpret_cast<float*>(ws + w.lse_part) : lse;
-  P.q_row0 = d.S - n_s;
-  P.n_qrows = n_s;
-  P.n_qtiles = (n_s + sa::kFlashBQ - 1) / sa::kFlashBQ;
-  {
-    Scope sc(SA_K_ROW_LSE, st);
-    s = dev(sa::launch_flash(1, false, P, st));
-    if (s == SA_OK && w.k_splits > 1)
-      s = dev(sa::launch_lse_combine(P.lse, lse, (size_t)d.n_bh * n_s, w.k_splits, st));
-  }
-  if (s != SA_OK) return s;
+  for (int m = 0; m < n_chunks; ++m) {
+    // chunk m: the last n_s rows of the m-th of n_chunks equal query segments
+    const int row_first = (int)((long long)d.S * (m + 1) / n_chunks) - n_s;
+    float* out_col = col_scores + (size_t)m * d.n_bh * n_cand;
+    float* out_slash = slash_scores + (size_t)m * d.n_bh * n_cand;
+    float* tok_col = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_col) : out_col;
+    float* tok_slash = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_slash) : out_slash;
 
-  // pass 2: recompute the probabilities and accumulate columns and diagonals
-  sa::ScoreParams C;
-  memset(&C, 0, sizeof(C));
-  C.q = static_cast<const uint16_t*>(q);
-  C.k = static_cast<const uint16_t*>(k);
-  C.lse = lse;
-  C.col = tok_col; C.slash = tok_slash;
-  C.partial = reinterpret_cast<float*>(ws + w.partial);
-  C.S = d.S; C.n_s = n_s; C.n_bh = d.n_bh; C.n_bkv = d.n_bkv; C.group = d.group;
-  C.scale_log2 = P.scale_log2;
-  {
-    Scope sc(SA_K_SCORE_ACCUM, st);
-    s = dev(sa::launch_score_accumulate(C, st));
+    // pass 1: log-sum-exp of every sampled row (flash sweep without V)
+    sa::FlashParams P = base_flash(d, q, k);
+    P.k_splits = sa::lse_key_splits(row_first, n_s, d.n_bh);
+    if (P.k_splits > kMaxKeySplits) P.k_splits = kMaxKeySplits;
+    P.lse = P.k_splits > 1 ? reinterpret_cast<float*>(ws + w.lse_part) : lse;
+    P.q_row0 = row_first;
+    P.n_qrows = n_s;
+    P.n_qtiles = (n_s + sa::kFlashBQ - 1) / sa::kFlashBQ;
+    {
+      Scope sc(SA_K_ROW_LSE, st);
+      s = dev(sa::launch_flash(1, false, P, st));
+      if (s == SA_OK && P.k_splits > 1)
+        s = dev(sa::launch_lse_combine(P.lse, lse, (size_t)d.n_bh * n_s, P.k_splits, st));
+    }
+    if (s != SA_OK) return s;
+
+    // pass 2: recompute the probabilities and accumulate columns and diagonals
+    sa::ScoreParams C;
+    memset(&C, 0, sizeof(C));
+    C.q = static_cast<const uint16_t*>(q);
+    C.k = static_cast<const uint16_t*>(k);
+    C.lse = lse;
+    C.col = tok_col; C.slash = tok_slash;
+    C.partial = reinterpret_cast<float*>(ws + w.partial);
+    C.S = d.S; C.n_s = n_s; C.n_bh = d.n_bh; C.n_bkv = d.n_bkv; C.group = d.group;
+    C.row_first = row_first;
+    C.scale_log2 = P.scale_log2;
+    {
+      Scope sc(SA_K_SCORE_ACCUM, st);
+      s = dev(sa::launch_score_accumulate(C, st));
+    }
+    if (s != SA_OK) return s;
+    {
+      Scope sc(SA_K_SCORE_FINAL, st);
+      s = dev(sa::launch_score_finalize(C, st));
+      // block_reduction: the per-token scores summed over blocks of blk keys / offsets
+      if (s == SA_OK && blk > 1) s = dev(sa::launch_block_reduce(tok_col, out_col, d.n_bh, d.S, blk, st));
+      if (s == SA_OK && blk > 1) s = dev(sa::launch_block_reduce(tok_slash, out_slash, d.n_bh, d.S, blk, st));
+    }
+    if (s != SA_OK) return s;
   }
-  if (s != SA_OK) return s;
-  Scope sc(SA_K_SCORE_FINAL, st);
-  s = dev(sa::launch_score_finalize(C, st));
-  if (s != SA_OK || blk == 1) return s;
-  // block_reduction: the per-token scores summed over blocks of blk keys / offsets
-  s = dev(sa::launch_block_reduce(tok_col, col_scores, d.n_bh, d.S, blk, st));
-  if (s != SA_OK) return s;
-  return dev(sa::launch_block_reduce(tok_slash, slash_scores, d.n_bh, d.S, blk, st));
+  return SA_OK;
 }
 
 sa_status sa_block_scores(const sa_shape* shape, int32_t granularity,
@@ -276,7 +302,7 @@ sa_status sa_block_scores(const sa_shape* shape, int32_t granularity,
 
 namespace {
 // both selections over n candidates per head (keys / offsets, or blocks of them)
-sa_status select_both(const sa_shape* shape, int granularity,
+sa_status select_both(const sa_shape* shape, int n_chunks, int granularity,
                       const float* col_scores, const float* slash_scores,
                       float alpha_c, float alpha_s,
                       int32_t* col_idx, int32_t* col_cnt,
@@ -284,10 +310,8 @@ sa_status select_both(const sa_shape* shape, int granularity,
   Dims d;
   sa_status s = check_shape(shape, &d);
   if (s != SA_OK) return s;
-  if (granularity != 1) {
-    s = check_granularity(granularity);
-    if (s != SA_OK) return s;
-  }
+  s = check_chunks(d, n_chunks, granularity);
+  if (s != SA_OK) return s;
   if (col_scores == nullptr || slash_scores == nullptr || col_idx == nullptr || col_cnt == nullptr ||
       slash_idx == nullptr || slash_cnt == nullptr)
     return SA_ERR_INVALID_ARG;
@@ -296,7 +320,8 @@ sa_status select_both(const sa_shape* shape, int granularity,
   hipStream_t st = static_cast<hipStream_t>(stream);
   Scope sc(SA_K_SELECT, st);
   sa::SelectParams P;
-  P.n_prob = d.n_bh; P.S = (d.S + granularity - 1) / granularity;
+  P.n_prob = n_chunks * d.n_bh;   // every (chunk, head) is a problem of its own
+  P.S = (d.S + granularity - 1) / granularity;
   P.scores = col_scores; P.idx = col_idx; P.cnt = col_cnt; P.alpha = alpha_c;
   s = dev(sa::launch_select(P, st));
   if (s != SA_OK) return s;
@@ -314,8 +339,8 @@ sa_status sa_select_strips(const sa_shape* shape,
                            int32_t* slash_idx, int32_t* slash_cnt,
                            void* workspace, size_t workspace_bytes, void* stream) {
   (void)workspace; (void)workspace_bytes;
-  return select_both(shape, 1, col_scores, slash_scores, alpha_c, alpha_s, col_idx, col_cnt, slash_idx, slash_cnt,
-                     stream);
+  return select_both(shape, 1, 1, col_scores, slash_scores, alpha_c, alpha_s, col_idx, col_cnt, slash_idx,
+                     slash_cnt, stream);
 }
 
 sa_status sa_select_blocks(const sa_shape* shape, int32_t granularity,
@@ -327,30 +352,41 @@ sa_status sa_select_blocks(const sa_shape* shape, int32_t granularity,
   (void)workspace; (void)workspace_bytes;
   if (granularity < 1) return SA_ERR_INVALID_ARG;
   if (granularity == 1) return SA_ERR_UNSUPPORTED;   // per-token selection is sa_select_strips
-  return select_both(shape, granularity, col_block_scores, slash_block_scores, alpha_c, alpha_s, col_blocks, col_cnt,
-                     slash_blocks, slash_cnt, stream);
+  return select_both(shape, 1, granularity, col_block_scores, slash_block_scores, alpha_c, alpha_s, col_blocks,
+                     col_cnt, slash_blocks, slash_cnt, stream);
+}
+
+sa_status sa_select_chunked(const sa_shape* shape, const sa_sampling* sampling,
+                            const float* col_scores, const float* slash_scores,
+                            float alpha_c, float alpha_s,
+                            int32_t* col_idx, int32_t* col_cnt,
+                            int32_t* slash_idx, int32_t* slash_cnt,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (sampling == nullptr) return SA_ERR_INVALID_ARG;
+  return select_both(shape, sampling->n_chunks, sampling->granularity, col_scores, slash_scores, alpha_c, alpha_s,
+                     col_idx, col_cnt, slash_idx, slash_cnt, stream);
 }
 
 }  // extern "C"
 
 namespace {
 // granularity 1: strip lists (per key / per offset); otherwise lists of blocks
-sa_status sparse_attn(const sa_shape* shape, int granularity, const void* q, const void* k, const void* v,
-                      const int32_t* col_idx, const int32_t* col_cnt,
-                      const int32_t* slash_idx, const int32_t* slash_cnt,
+sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
+                      const void* q, const void* k, const void* v,
+                      const int32_t* col_idx_all, const int32_t* col_cnt_all,
+                      const int32_t* slash_idx_all, const int32_t* slash_cnt_all,
                       int32_t local_window,
                       void* out, int out_dtype, float* out_lse, uint64_t* tiles,
                       void* workspace, size_t workspace_bytes, void* stream) {
   Dims d;
   sa_status s = check_shape(shape, &d);
   if (s != SA_OK) return s;
+  s = check_chunks(d, n_chunks, granularity);
+  if (s != SA_OK) return s;
   const bool blocks = granularity != 1;
-  if (blocks) {
-    s = check_granularity(granularity);
-    if (s != SA_OK) return s;
-  }
-  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || col_idx == nullptr ||
-      col_cnt == nullptr || slash_idx == nullptr || slash_cnt == nullptr)
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || col_idx_all == nullptr ||
+      col_cnt_all == nullptr || slash_idx_all == nullptr || slash_cnt_all == nullptr)
     return SA_ERR_INVALID_ARG;
   if (local_window < 1) return SA_ERR_INVALID_ARG;
   if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
@@ -360,7 +396,20 @@ sa_status sparse_attn(const sa_shape* shape, int granularity, const void* q, con
   if (s != SA_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
+  if (tiles != nullptr) {
+    s = dev(sa::launch_fill_u32(reinterpret_cast<uint32_t*>(tiles), 2 * (size_t)d.n_bh, 0u, st));
+    if (s != SA_OK) return s;
+  }
+  const size_t n_cand = (size_t)(d.S + granularity - 1) / granularity;   // list capacity per head
+  const int n_qtiles_all = (d.S + sa::kFlashBQ - 1) / sa::kFlashBQ;
 
+  // One pass per chunk: the strips selected from chunk m mask the query rows of
+  // segment m (merge_index with itv = S / chunk_n); a single chunk is the whole matrix.
+  for (int m = 0; m < n_chunks; ++m) {
+  const int32_t* col_idx = col_idx_all + (size_t)m * d.n_bh * n_cand;
+  const int32_t* slash_idx = slash_idx_all + (size_t)m * d.n_bh * n_cand;
+  const int32_t* col_cnt = col_cnt_all + (size_t)m * d.n_bh;
+  const int32_t* slash_cnt = slash_cnt_all + (size_t)m * d.n_bh;
   sa::MaskPrepParams M;
   {
     Scope sc(SA_K_MASK_PREP, st);
@@ -394,7 +443,7 @@ sa_status sparse_attn(const sa_shape* shape, int granularity, const void* q, con
     if (s != SA_OK) return s;
 
     // V^T for the contiguous (slash / window) tiles
-    s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
+    if (m == 0) s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
     if (s != SA_OK) return s;
 
     // merge_index, column side: compact K rows and V^T columns of the kept keys, per query head
@@ -414,13 +463,10 @@ sa_status sparse_attn(const sa_shape* shape, int granularity, const void* q, con
     G.idx_pad = nullptr;
     s = dev(sa::launch_gather_transpose(G, st));
     if (s != SA_OK) return s;
-
-  }
-  if (tiles != nullptr) {
-    s = dev(sa::launch_fill_u32(reinterpret_cast<uint32_t*>(tiles), 2 * (size_t)d.n_bh, 0u, st));
-    if (s != SA_OK) return s;
   }
   sa::FlashParams P = base_flash(d, q, k);
+  P.qtile0 = (int)((long long)n_qtiles_all * m / n_chunks);
+  P.n_qtiles = (int)((long long)n_qtiles_all * (m + 1) / n_chunks) - P.qtile0;
   P.vt = reinterpret_cast<const uint16_t*>(ws + w.vt);
   P.out = out; P.lse = out_lse;
   P.kc = reinterpret_cast<const uint16_t*>(ws + w.kc);
@@ -433,7 +479,10 @@ sa_status sparse_attn(const sa_shape* shape, int granularity, const void* q, con
   P.cidx_stride = d.S_pad; P.cb_words = w.cb_words; P.rb_words = w.rb_words;
   P.dlist_stride = w.dlist_stride; P.off_max = w.off_max;
   Scope sc(SA_K_SPARSE_FLASH, st);
-  return dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
+  s = dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
+  if (s != SA_OK) return s;
+  }
+  return SA_OK;
 }
 }  // namespace
 
@@ -445,7 +494,7 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
                          int32_t local_window,
                          void* out, int out_dtype, float* out_lse, uint64_t* tiles,
                          void* workspace, size_t workspace_bytes, void* stream) {
-  return sparse_attn(shape, 1, q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window, out, out_dtype,
+  return sparse_attn(shape, 1, 1, q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window, out, out_dtype,
                      out_lse, tiles, workspace, workspace_bytes, stream);
 }
 
@@ -458,8 +507,20 @@ sa_status sa_block_sparse_attn(const sa_shape* shape, int32_t granularity,
                                void* workspace, size_t workspace_bytes, void* stream) {
   if (granularity < 1) return SA_ERR_INVALID_ARG;
   if (granularity == 1) return SA_ERR_UNSUPPORTED;   // per-token strips are sa_sparse_attn
-  return sparse_attn(shape, granularity, q, k, v, col_blocks, col_cnt, slash_blocks, slash_cnt, local_window, out,
+  return sparse_attn(shape, 1, granularity, q, k, v, col_blocks, col_cnt, slash_blocks, slash_cnt, local_window, out,
                      out_dtype, out_lse, tiles, workspace, workspace_bytes, stream);
+}
+
+sa_status sa_sparse_attn_chunked(const sa_shape* shape, const sa_sampling* sampling,
+                                 const void* q, const void* k, const void* v,
+                                 const int32_t* col_idx, const int32_t* col_cnt,
+                                 const int32_t* slash_idx, const int32_t* slash_cnt,
+                                 int32_t local_window,
+                                 void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (sampling == nullptr) return SA_ERR_INVALID_ARG;
+  return sparse_attn(shape, sampling->n_chunks, sampling->granularity, q, k, v, col_idx, col_cnt, slash_idx,
+                     slash_cnt, local_window, out, out_dtype, out_lse, tiles, workspace, workspace_bytes, stream);
 }
 
 sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
@@ -525,6 +586,6 @@ const char* sa_status_string(int status) {
   }
 }
 
-int sa_version(void) { return 110; }
+int sa_version(void) { return 120; }
 
 }  // extern "C"

@@ -19,6 +19,7 @@ struct FlashParams {
   int n_bh, n_bkv, group;   // batch*q-heads, batch*kv-heads, q heads per kv head
   float scale_log2;         // softmax scale * log2(e)
   int n_qtiles;             // 256-row query tiles to process
+  int qtile0;               // strip-masked mode: the first of them (a segment of the queries)
   int q_row0, n_qrows;      // first query row and number of rows (sampled rows in mode 1)
   int k_splits;             // mode 1: the keys of a query tile are cut into this many workgroups (>= 1);
                             // lse is then [k_splits, n_bh, n_qrows] partial values (launch_lse_combine)
@@ -37,7 +38,7 @@ struct FlashParams {
 
 // mode 0: dense causal; 1: row log-sum-exp of rows [q_row0, q_row0+n_qrows); 2: strip mask
 hipError_t launch_flash(int mode, bool out_f32, const FlashParams& P, hipStream_t st);
-int lse_key_splits(int S, int n_s, int n_bh);
+int lse_key_splits(int row_first, int n_s, int n_bh);
 hipError_t launch_lse_combine(const float* part, float* out, size_t n, int k, hipStream_t st);
 
 // out[g][d][c] = src[kv(g)][idx ? idx[g][c] : c][d] for c < cnt (zero beyond, up to C_pad);
@@ -86,6 +87,7 @@ struct ScoreParams {
   float* slash;             // [n_bh, S]
   float* partial;           // workspace for slash partial sums
   int S, n_s, n_bh, n_bkv, group;
+  int row_first;            // the sampled rows are [row_first, row_first + n_s)
   float scale_log2;
   int n_kblocks, n_chunks, chunk_rows, win;   // win = floats per (key block, chunk) partial
 };

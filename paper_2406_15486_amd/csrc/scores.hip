@@ -44,9 +44,10 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
   const int ql = lane & 31, hf = lane >> 5;
   const int kb = blockIdx.x, ch = blockIdx.y, bh = blockIdx.z;
   const int S = P.S;
-  const int r0 = S - P.n_s;
+  const int r0 = P.row_first;                       // sampled rows [r0, r_end)
+  const int r_end = r0 + P.n_s;
   const int row0 = r0 + ch * QC;                    // first row of the chunk
-  const int row_end = min(row0 + QC, S);            // one past the last row
+  const int row_end = min(row0 + QC, r_end);        // one past the last row
   const int j0 = kb * KB;
   if (row_end - 1 < j0) return;                     // chunk entirely above these keys
   const int jw = j0 + 64 * wave;
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
     if (i1 < S) pq1 = *reinterpret_cast<const uint4*>(qbase + (size_t)i1 * kHeadDim + qcol_t * 8);
     if (tid < 32) {
       int i = rb + tid;
-      pl = (i < S) ? lbase[i - r0] * kLog2e : 0.f;
+      pl = (i < r_end) ? lbase[i - r0] * kLog2e : 0.f;
     }
   };
   auto store_block = [&](char* st) {
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
       for (int sb = 0; sb < 2; ++sb) {
         const int jsb = jw + 32 * sb;
         // element r: query row rb + 8*(r/4) + 4*hf + r%4, key jsb + ql
-        const bool edge = (rb < jsb + 32) || (rb + 32 > S);
+        const bool edge = (rb < jsb + 32) || (rb + 32 > r_end);
         const int j_me = jsb + ql;
         // straight-line code: all exponentials first, the (rare) edge mask in one
         // wave-uniform branch, then the sums
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             int i = rb + 8 * (r >> 2) + 4 * hf + (r & 3);
-            p[r] = (i >= j_me && i < S) ? p[r] : 0.f;
+            p[r] = (i >= j_me && i < r_end) ? p[r] : 0.f;
           }
         }
         float csum = 0.f;
@@ -247,11 +248,11 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(ScoreParams P, cons
   const int x = blockIdx.x * 256 + threadIdx.x;
   const int S = P.S;
   if (x >= S) return;
-  const int r0 = S - P.n_s;
+  const int r0 = P.row_first;
   double c = 0.0, s = 0.0;
   for (int ch = 0; ch < P.n_chunks; ++ch) {
     int row0 = r0 + ch * QC;
-    int row_end = min(row0 + QC, S);
+    int row_end = min(row0 + QC, r0 + P.n_s);
     // column x
     if (row_end - 1 >= (x / KB) * KB) c += (double)colpart[((size_t)bh * P.n_chunks + ch) * S + x];
     // offset x: slot = x - row0 + KB kb + (KB - 1) in [0, WIN)

@@ -111,7 +111,11 @@ def test_sampling_validation(lib, B):
     assert call(B._CSampling(0, 1, 1)) == SA_INVALID
     assert call(B._CSampling(1024, 1, 1)) == SA_INVALID                     # more rows than the sequence
     assert call(B._CSampling(50, 1, 1)) == SA_INVALID                       # not a multiple of 32
-    assert call(B._CSampling(64, 2, 1)) == SA_UNSUPPORTED                   # chunk_n > 1 not built yet
+    assert call(B._CSampling(64, 3, 1)) == SA_UNSUPPORTED                   # 512 rows do not split into 3 x 256
+    assert call(B._CSampling(288, 2, 1)) == SA_INVALID                      # more rows than a segment holds
+    assert call(B._CSampling(64, 2, 1)) == SA_WORKSPACE                     # valid; 16 bytes is too small
+    assert lib.sa_sample_scores(ctypes.byref(sh), ctypes.byref(B._CSampling(64, 2, 1)), FAKE, FAKE, FAKE, FAKE,
+                                FAKE, FAKE, 1 << 40, None) == SA_UNSUPPORTED   # no row_lse output with chunks
     assert call(B._CSampling(64, 1, 100)) == SA_UNSUPPORTED                 # block sizes: 64, 128, 256
     assert call(B._CSampling(64, 1, 0)) == SA_INVALID
     assert call(B._CSampling(64, 1, 128)) == SA_WORKSPACE                   # valid; 16 bytes is too small
@@ -174,6 +178,31 @@ def test_block_entry_points_validation(lib, B):
     s1 = lib.sa_workspace_bytes(0, ctypes.byref(sh), ctypes.byref(B._CSampling(64, 1, 1)))
     s128 = lib.sa_workspace_bytes(0, ctypes.byref(sh), ctypes.byref(B._CSampling(64, 1, 128)))
     assert s128 >= s1 + 2 * 4 * 512 * 4
+
+
+def test_chunked_entry_points_validation(lib, B):
+    sh = _shape(B)
+
+    def sel(sm, ac=0.5):
+        return lib.sa_select_chunked(ctypes.byref(sh), ctypes.byref(sm) if sm is not None else None, FAKE, FAKE,
+                                     ctypes.c_float(ac), ctypes.c_float(0.5), FAKE, FAKE, FAKE, FAKE, None, 0, None)
+
+    assert sel(None) == SA_INVALID
+    assert sel(B._CSampling(0, 0, 1)) == SA_INVALID
+    assert sel(B._CSampling(0, 3, 1)) == SA_UNSUPPORTED
+    assert sel(B._CSampling(0, 2, 100)) == SA_UNSUPPORTED
+    assert sel(B._CSampling(0, 2, 1), ac=-1.0) == SA_INVALID
+
+    def attn(sm, window=4, ws_bytes=16):
+        return lib.sa_sparse_attn_chunked(ctypes.byref(sh), ctypes.byref(sm) if sm is not None else None, FAKE, FAKE,
+                                          FAKE, FAKE, FAKE, FAKE, FAKE, window, FAKE, 0, None, None, FAKE, ws_bytes,
+                                          None)
+
+    assert attn(None) == SA_INVALID
+    assert attn(B._CSampling(0, 3, 1)) == SA_UNSUPPORTED
+    assert attn(B._CSampling(0, 2, 1), window=0) == SA_INVALID
+    assert attn(B._CSampling(0, 2, 1)) == SA_WORKSPACE
+    assert attn(B._CSampling(0, 2, 128)) == SA_WORKSPACE
 
 
 def test_profile_read_before_enable(lib):

@@ -1,0 +1,181 @@
+"""GPU parity of the chunk_n > 1 entry points (Algorithm 1 with itv = S / chunk_n)
+against the fp64 oracle, on the same seeded inputs.  Tolerances as for the
+single-chunk path: scores |gpu - oracle| <= 1e-4 * oracle + 1e-6, index sets
+bit-exact on the same fp32 scores, outputs max-abs <= 2e-2, mean-abs <= 2e-3.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sample_attention as O
+from sa_inputs import CONFIGS, bf16_bits_to_f32, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+
+
+def _say(msg):
+    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+
+
+def _dev(bits):
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16)
+    return t[None].contiguous().cuda()
+
+
+def _f64(bits):
+    return bf16_bits_to_f32(bits).astype(np.float64)
+
+
+def _inputs(name, S, Hq, Hkv, seed=7, gain=None, **kw):
+    from dataclasses import replace
+    wl = replace(CONFIGS[name], seq_len=S, n_q_heads=Hq, n_kv_heads=Hkv, **kw)
+    if gain:
+        wl = wl.with_structure_gain(gain)
+    return wl, make_inputs(wl, seed=seed)
+
+
+def _check_out(got, want, what):
+    err = np.abs(got.astype(np.float64) - want)
+    _say(f"{what}: max-abs {err.max():.3e} mean-abs {err.mean():.3e}")
+    assert np.isfinite(got).all(), what
+    assert err.max() <= MAX_ABS, (what, err.max())
+    assert err.mean() <= MEAN_ABS, (what, err.mean())
+
+
+def _score_tol(got, want, what):
+    err = np.abs(got.astype(np.float64) - want)
+    worst = (err / (1e-4 * np.abs(want) + 1e-6)).max()
+    _say(f"{what}: worst err/bound {worst:.3f}")
+    assert worst <= 1.0, (what, worst)
+
+
+@pytest.mark.parametrize("S,Hq,Hkv,C,n_s,blk", [(1024, 2, 1, 2, 64, 1), (3072, 4, 2, 4, 128, 1), (2048, 2, 2, 2, 1024, 1),
+                                                (2048, 2, 1, 4, 128, 128)])
+def test_chunked_scores_match_oracle(S, Hq, Hkv, C, n_s, blk):
+    import paper_2406_15486_amd as sa
+    _say(f"chunked scores S={S} Hq={Hq} C={C} n_s={n_s} blk={blk}")
+    wl, x = _inputs("glm8k", S, Hq, Hkv, n_sinks=8)
+    q, k = _dev(x["q"]), _dev(x["k"])
+    col, slash = sa.sa_sample_scores(q, k, n_s, granularity=blk, n_chunks=C)
+    col2, slash2 = sa.sa_sample_scores(q, k, n_s, granularity=blk, n_chunks=C)
+    torch.cuda.synchronize()
+    n = (S + blk - 1) // blk
+    assert col.shape == (C, Hq, n)
+    assert torch.equal(col, col2) and torch.equal(slash, slash2), "run-to-run bits differ"
+    qf, kf = _f64(x["q"]), _f64(x["k"])
+    G = Hq // Hkv
+    for h in range(Hq):
+        wc, ws = O.sample_scores_chunked(qf[h], kf[h // G], n_s, C)
+        for m in range(C):
+            want_c = wc[m] if blk == 1 else O.block_reduce(wc[m], blk)
+            want_s = ws[m] if blk == 1 else O.block_reduce(ws[m], blk)
+            _score_tol(col[m, h].cpu().numpy(), want_c, f"col chunk {m} h{h}")
+            _score_tol(slash[m, h].cpu().numpy(), want_s, f"slash chunk {m} h{h}")
+            assert abs(float(col[m, h].double().sum()) - n_s) < 1e-3 * n_s
+    # the last chunk is the single-chunk path
+    c1, s1 = sa.sa_sample_scores(q, k, n_s, granularity=blk)
+    torch.cuda.synchronize()
+    assert torch.equal(c1, col[C - 1]) and torch.equal(s1, slash[C - 1])
+
+
+def test_select_chunked_bit_exact():
+    import paper_2406_15486_amd as sa
+    _say("select chunked")
+    S, C, n = 1536, 3, 4
+    rng = np.random.default_rng(3)
+    a = (rng.random((C, n, S)) ** 6).astype(np.float32)
+    b = np.exp(rng.standard_normal((C, n, S)) * 3).astype(np.float32)
+    a[1, :, 512:] = 0.0                          # a chunk whose sampled rows see only a prefix
+    sh = sa.Shape(1, n, n, S)
+    ci, cc, si, sc = sa.sa_select_chunked(torch.from_numpy(a).cuda(), torch.from_numpy(b).cuda(), 0.9, 0.7, sh, C)
+    torch.cuda.synchronize()
+    for m in range(C):
+        for h in range(n):
+            for idx, cnt, scores, alpha in ((ci, cc, a, 0.9), (si, sc, b, 0.7)):
+                want = O.select(scores[m, h], float(np.float32(alpha)))
+                assert int(cnt[m, h]) == len(want)
+                assert np.array_equal(idx[m, h, :int(cnt[m, h])].cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("S,Hq,Hkv,C,w,blk", [(1024, 2, 1, 2, 64, 1), (3072, 2, 2, 4, 128, 1), (1536, 2, 1, 3, 1, 128),
+                                              (2048, 2, 2, 2, 200, 64)])
+def test_chunked_attn_random_lists(S, Hq, Hkv, C, w, blk):
+    import paper_2406_15486_amd as sa
+    _say(f"chunked attn random S={S} C={C} w={w} blk={blk}")
+    wl, x = _inputs("glm8k", S, Hq, Hkv, n_sinks=8)
+    n = (S + blk - 1) // blk
+    rng = np.random.default_rng(S + C + blk)
+    Ic = [[np.sort(rng.choice(n, rng.integers(0, n // 3 + 1), replace=False)) for _ in range(Hq)] for _ in range(C)]
+    Is = [[np.sort(rng.choice(n, rng.integers(0, n // 5 + 1), replace=False)) for _ in range(Hq)] for _ in range(C)]
+    ci = torch.zeros(C, Hq, n, dtype=torch.int32)
+    si = torch.zeros(C, Hq, n, dtype=torch.int32)
+    cc = torch.zeros(C, Hq, dtype=torch.int32)
+    sc = torch.zeros(C, Hq, dtype=torch.int32)
+    for m in range(C):
+        for h in range(Hq):
+            ci[m, h, :len(Ic[m][h])] = torch.from_numpy(Ic[m][h].astype(np.int32))
+            si[m, h, :len(Is[m][h])] = torch.from_numpy(Is[m][h].astype(np.int32))
+            cc[m, h], sc[m, h] = len(Ic[m][h]), len(Is[m][h])
+    out, lse, tiles = sa.sa_sparse_attn_chunked(_dev(x["q"]), _dev(x["k"]), _dev(x["v"]), ci.cuda(), cc.cuda(),
+                                                si.cuda(), sc.cuda(), w, C, granularity=blk,
+                                                want_lse=True, want_tiles=True)
+    torch.cuda.synchronize()
+    qf, kf, vf = _f64(x["q"]), _f64(x["k"]), _f64(x["v"])
+    G = Hq // Hkv
+    for h in range(Hq):
+        want, wlse = O.chunked_masked_attn(qf[h], kf[h // G], vf[h // G], [Ic[m][h] for m in range(C)],
+                                           [Is[m][h] for m in range(C)], w, C, blk=blk)
+        _check_out(out[0, h].float().cpu().numpy(), want, f"chunked attn h{h}")
+        assert np.abs(lse[h].cpu().numpy() - wlse).max() < 2e-3
+    assert (tiles.cpu().numpy() > 0).all()
+
+
+@pytest.mark.parametrize("name,S,Hq,Hkv,C,gain,blk", [("glm32k", 2048, 2, 1, 2, 5.0, 1), ("glm32k", 4096, 4, 2, 4, None, 128)])
+def test_chunked_pipeline_end_to_end(name, S, Hq, Hkv, C, gain, blk):
+    import paper_2406_15486_amd as sa
+    _say(f"chunked pipeline {name} S={S} C={C} gain={gain} blk={blk}")
+    n_s, alpha = 128, 0.95
+    wl, x = _inputs(name, S, Hq, Hkv, gain=gain)
+    w = wl.window
+    q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    sh = sa.Shape(1, Hq, Hkv, S)
+    col, slash = sa.sa_sample_scores(q, k, n_s, granularity=blk, n_chunks=C)
+    ci, cc, si, sc = sa.sa_select_chunked(col, slash, alpha, alpha, sh, C, blk)
+    out, _, _ = sa.sa_sparse_attn_chunked(q, k, v, ci, cc, si, sc, w, C, blk)
+    out2 = sa.chunked_sample_attention(q, k, v, n_s, C, alpha, alpha, w, blk)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    qf, kf, vf = _f64(x["q"]), _f64(x["k"]), _f64(x["v"])
+    G = Hq // Hkv
+    a32 = float(np.float32(alpha))
+    for h in range(Hq):
+        res = O.chunked_sample_attention(qf[h], kf[h // G], vf[h // G], n_s, C, a32, a32, w, blk=blk)
+        gc = [ci[m, h, :int(cc[m, h])].cpu().numpy() for m in range(C)]
+        gs = [si[m, h, :int(sc[m, h])].cpu().numpy() for m in range(C)]
+        for m in range(C):
+            for got, want, scores, nm in ((gc[m], res["col_idx"][m], res["col"][m], "col"),
+                                          (gs[m], res["slash_idx"][m], res["slash"][m], "slash")):
+                diff = np.setxor1d(got, want)
+                if len(diff):
+                    cut = scores[want].min()
+                    gap = np.abs(scores[diff] - cut).max() / cut
+                    _say(f"h{h} chunk {m} {nm}: {len(diff)} differing, gap {gap:.2e}")
+                    assert gap < 1e-3, (nm, h, m, gap)
+        want_out, _ = O.chunked_masked_attn(qf[h], kf[h // G], vf[h // G], gc, gs, w, C, blk=blk)
+        _check_out(out[0, h].float().cpu().numpy(), want_out, f"chunked pipeline out h{h}")
+
+
+def test_one_chunk_through_the_chunked_entry_points_is_the_plain_path():
+    import paper_2406_15486_amd as sa
+    _say("chunked with C=1 vs plain")
+    S, Hq = 1300, 2
+    wl, x = _inputs("glm8k", S, Hq, 1, n_sinks=8)
+    q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    a = sa.chunked_sample_attention(q, k, v, 64, 1, 0.9, 0.9, 32)
+    b = sa.sample_attention(q, k, v, 64, 0.9, 0.9, 32)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
