@@ -291,26 +291,31 @@ def main() -> int:
     block_runs = []
     if not args.no_block:
         blk = 128
-        for bn_s in sorted({n_s, min(128, S)}, reverse=True):
-            bplan = sa.SampleAttentionPlan(shape, bn_s, granularity=blk)
+        variants = [(bn_s, 1) for bn_s in sorted({n_s, min(128, S)}, reverse=True)]
+        if S % 512 == 0 and S >= 1024:
+            variants.append((128, 2))         # Algorithm 1 as printed: chunk_n = 2, 128 rows per chunk
+        for bn_s, n_chunks in variants:
+            bplan = sa.SampleAttentionPlan(shape, bn_s, granularity=blk, n_chunks=n_chunks)
             for a in wl.alphas:
                 bplan.run(q, k, v, a, a, w)          # warm
                 torch.cuda.synchronize()
                 sa.sa_profile_enable(True)
                 bplan.run(q, k, v, a, a, w)
                 torch.cuda.synchronize()
-                t = {n: float(np.mean(sa.sa_profile_read(n))) for n in
+                # a kernel runs once per chunk: the step's time is the sum of its launches
+                t = {n: float(np.sum(sa.sa_profile_read(n))) for n in
                      ("row_lse", "score_accum", "score_final", "select", "mask_prep", "sparse_flash")}
                 tl = bplan.tiles.cpu().numpy().astype(np.int64)
                 cca, sca = bplan.col_cnt.cpu().numpy(), bplan.slash_cnt.cpu().numpy()
                 total = sum(t.values())
+                # head 0, last chunk: the mask of the bottom segment of the queries
+                c0 = bplan.col_idx.reshape(-1, *bplan.col_idx.shape[-2:])[-1, 0, :int(cca.reshape(n_chunks, -1)[-1, 0])]
+                s0 = bplan.slash_idx.reshape(-1, *bplan.slash_idx.shape[-2:])[-1, 0, :int(sca.reshape(n_chunks, -1)[-1, 0])]
                 block_runs.append({
-                    "granularity": blk, "n_sample_rows": bn_s, "alpha": a, "ms_layer": total,
+                    "granularity": blk, "n_sample_rows": bn_s, "n_chunks": n_chunks, "alpha": a, "ms_layer": total,
                     "sparse_flash_ms": t["sparse_flash"],
                     "computed_tile_fraction": float(tl.sum()) / dense_tiles,
-                    "block_mask_density_head0": block_mask_density(
-                        S, bplan.col_idx[0, :int(cca[0])].cpu().numpy(),
-                        bplan.slash_idx[0, :int(sca[0])].cpu().numpy(), w, blk),
+                    "block_mask_density_head0": block_mask_density(S, c0.cpu().numpy(), s0.cpu().numpy(), w, blk),
                     "mean_k_c_blocks": float(cca.mean()), "mean_k_s_blocks": float(sca.mean()),
                     "speedup_vs_dense": (dense_ms / total) if dense_ms else None,
                     "flash_tflops": float(tl.sum()) * TILE_FLOP / (t["sparse_flash"] * 1e-3) / 1e12,

@@ -402,12 +402,12 @@ class SampleAttentionPlan:
     and nothing else (no allocation, no host synchronisation)."""
 
     def __init__(self, shape: Shape, n_sample_rows: int, device="cuda", out_dtype: int = SA_OUT_BF16,
-                 granularity: int = 1):
+                 granularity: int = 1, n_chunks: int = 1):
         lib = load_library()
         self.lib, self.shape, self.n_s, self.out_dtype = lib, shape, n_sample_rows, out_dtype
-        self.granularity = granularity
+        self.granularity, self.n_chunks = granularity, n_chunks
         self.cs = shape.c()
-        self.sm = _CSampling(n_sample_rows, 1, granularity)
+        self.sm = _CSampling(n_sample_rows, n_chunks, granularity)
         ops = (SA_OP_SAMPLE_SCORES, SA_OP_SPARSE_ATTN if granularity == 1 else SA_OP_BLOCK_SPARSE_ATTN,
                SA_OP_DENSE_ATTN)
         sizes = [int(lib.sa_workspace_bytes(op, ctypes.byref(self.cs), ctypes.byref(self.sm))) for op in ops]
@@ -415,12 +415,13 @@ class SampleAttentionPlan:
             raise ValueError("invalid shape or sampling for this library")
         need = max(sizes)
         n, S = shape.n_bh, n_blocks(shape.seq_len, granularity)   # candidates per head and direction
+        lead = (n_chunks,) if n_chunks != 1 else ()               # chunked arrays: [chunk_n, heads, ...]
         self.ws = torch.empty(need, dtype=torch.uint8, device=device)
-        self.col = torch.empty(n, S, dtype=torch.float32, device=device)
+        self.col = torch.empty(*lead, n, S, dtype=torch.float32, device=device)
         self.slash = torch.empty_like(self.col)
-        self.col_idx = torch.empty(n, S, dtype=torch.int32, device=device)
+        self.col_idx = torch.empty(*lead, n, S, dtype=torch.int32, device=device)
         self.slash_idx = torch.empty_like(self.col_idx)
-        self.col_cnt = torch.empty(n, dtype=torch.int32, device=device)
+        self.col_cnt = torch.empty(*lead, n, dtype=torch.int32, device=device)
         self.slash_cnt = torch.empty_like(self.col_cnt)
         self.tiles = torch.zeros(n, dtype=torch.int64, device=device)
         odt = torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16
@@ -436,6 +437,12 @@ class SampleAttentionPlan:
                                            self.ws.numel(), _stream()), "sa_sample_scores")
 
     def select(self, alpha_c, alpha_s):
+        if self.n_chunks != 1:
+            self._ok(self.lib.sa_select_chunked(ctypes.byref(self.cs), ctypes.byref(self.sm), _ptr(self.col),
+                                                _ptr(self.slash), ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
+                                                _ptr(self.col_idx), _ptr(self.col_cnt), _ptr(self.slash_idx),
+                                                _ptr(self.slash_cnt), None, 0, _stream()), "sa_select_chunked")
+            return
         if self.granularity != 1:
             self._ok(self.lib.sa_select_blocks(ctypes.byref(self.cs), self.granularity, _ptr(self.col),
                                                _ptr(self.slash), ctypes.c_float(alpha_c), ctypes.c_float(alpha_s),
@@ -448,6 +455,14 @@ class SampleAttentionPlan:
                                            _ptr(self.slash_cnt), None, 0, _stream()), "sa_select_strips")
 
     def attend(self, q, k, v, window):
+        if self.n_chunks != 1:
+            self._ok(self.lib.sa_sparse_attn_chunked(ctypes.byref(self.cs), ctypes.byref(self.sm), _ptr(q), _ptr(k),
+                                                     _ptr(v), _ptr(self.col_idx), _ptr(self.col_cnt),
+                                                     _ptr(self.slash_idx), _ptr(self.slash_cnt), int(window),
+                                                     _ptr(self.out), self.out_dtype, None, _ptr(self.tiles),
+                                                     _ptr(self.ws), self.ws.numel(), _stream()),
+                     "sa_sparse_attn_chunked")
+            return
         if self.granularity != 1:
             self._ok(self.lib.sa_block_sparse_attn(ctypes.byref(self.cs), self.granularity, _ptr(q), _ptr(k), _ptr(v),
                                                    _ptr(self.col_idx), _ptr(self.col_cnt), _ptr(self.slash_idx),

@@ -146,3 +146,52 @@ def test_glm128k_block_granularity():
         err = np.abs(out[0, h].float().cpu().numpy()[rows] - want)
         _say(f"glm128k block: out head {h}: max-abs {err.max():.3e} mean-abs {err.mean():.3e}")
         assert err.max() <= 2e-2 and err.mean() <= 2e-3
+
+
+def test_glm128k_two_chunks_block_granularity():
+    """The benchmark workload as Algorithm 1 prints it: chunk_n = 2, blk = 128,
+    128 sampled rows at the bottom of each half of the queries."""
+    import paper_2406_15486_amd as sa
+    wl = CONFIGS["glm128k"]
+    S, Hq, Hkv, w = wl.seq_len, wl.n_q_heads, wl.n_kv_heads, wl.window
+    blk, n_s, alpha, C = 128, 128, 0.95, 2
+    G = Hq // Hkv
+    nb = (S + blk - 1) // blk
+    _say(f"glm128k 2 chunks: generating inputs S={S}")
+    x = make_inputs(wl)
+    q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    sh = sa.Shape(1, Hq, Hkv, S)
+    col, slash = sa.sa_sample_scores(q, k, n_s, granularity=blk, n_chunks=C)
+    ci, cc, si, sc = sa.sa_select_chunked(col, slash, alpha, alpha, sh, C, blk)
+    out, _, tiles = sa.sa_sparse_attn_chunked(q, k, v, ci, cc, si, sc, w, C, blk, want_tiles=True)
+    torch.cuda.synchronize()
+    col, slash = col.cpu().numpy(), slash.cpu().numpy()
+    ci, cc, si, sc = ci.cpu().numpy(), cc.cpu().numpy(), si.cpu().numpy(), sc.cpu().numpy()
+    assert col.shape == (C, Hq, nb)
+    a32 = float(np.float32(alpha))
+    for m in range(C):
+        assert np.all(np.abs(col[m].astype(np.float64).sum(1) - n_s) < 2e-3 * n_s)
+        assert np.all(np.abs(slash[m].astype(np.float64).sum(1) - n_s) < 2e-3 * n_s)
+        assert not col[m, :, (m + 1) * nb // C:].any()           # nothing after the chunk's segment
+        for h in range(Hq):
+            assert np.array_equal(ci[m, h, :cc[m, h]], O.select(col[m, h], a32)), ("col", m, h)
+            assert np.array_equal(si[m, h, :sc[m, h]], O.select(slash[m, h], a32)), ("slash", m, h)
+    _say(f"glm128k 2 chunks: selection bit-exact; mean k_c {cc.mean(1)} k_s {sc.mean(1)} of {nb}")
+    h = 17
+    wc, ws = O.sample_scores_chunked(_f64(x["q"][h]), _f64(x["k"][h // G]), n_s, C)
+    for m in range(C):
+        for got, want, nm in ((col[m, h], O.block_reduce(wc[m], blk), "col"),
+                              (slash[m, h], O.block_reduce(ws[m], blk), "slash")):
+            worst = (np.abs(got - want) / (1e-4 * np.abs(want) + 1e-6)).max()
+            _say(f"   chunk {m} {nm} blocks: worst err/bound {worst:.3f}")
+            assert worst <= 1.0, (nm, m, worst)
+    rows = np.unique(np.concatenate([np.linspace(0, S - 1, 40).astype(np.int64),
+                                     [0, S // 2 - 1, S // 2, S // 2 + 255, S - 1]]))
+    for h in (6, 29):
+        want, _ = O.chunked_masked_attn(_f64(x["q"][h]), _f64(x["k"][h // G]), _f64(x["v"][h // G]),
+                                        [ci[m, h, :cc[m, h]] for m in range(C)],
+                                        [si[m, h, :sc[m, h]] for m in range(C)], w, C, rows=rows, blk=blk)
+        err = np.abs(out[0, h].float().cpu().numpy()[rows] - want)
+        _say(f"glm128k 2 chunks: out head {h}: max-abs {err.max():.3e} mean-abs {err.mean():.3e}")
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3
+    assert (tiles.cpu().numpy() > 0).all()
