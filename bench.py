@@ -161,6 +161,8 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="skip the alpha sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block", action="store_true", help="skip the block-granularity runs")
+    ap.add_argument("--alpha-grid", action="store_true",
+                    help="also run a grid of separate column / slash thresholds (alpha_c x alpha_s)")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates HBM byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=8.0,
@@ -256,6 +258,22 @@ def main() -> int:
         dense_kernel_tflops = dense_tiles * TILE_FLOP / (float(np.mean(dk)) * 1e-3) / 1e12
         log(f"dense kernel {np.mean(dk):.3f} ms (+{np.mean(dt):.3f} ms V^T) -> {dense_kernel_tflops:.1f} TFLOP/s")
 
+    # Recall of a mask on row i = sum of the dense softmax over the kept keys
+    # = exp(lse_masked_i - lse_dense_i); its minimum over rows is the CRA of the mask
+    # (Sec. 3.3).  Both log-sum-exps are optional outputs of the attention kernels.
+    dense_lse = None
+    if dense_ms is not None and (not args.no_sweep or not args.no_block or args.alpha_grid):
+        plan.lse = torch.empty(Hq, S, dtype=torch.float32, device="cuda")
+        plan.dense(q, k, v)
+        torch.cuda.synchronize()
+        dense_lse = plan.lse.clone()
+
+    def recall_stats(lse_masked):
+        if dense_lse is None:
+            return {}
+        r = torch.exp(lse_masked - dense_lse)
+        return {"recall_mean": float(r.mean()), "cra_min": float(r.min())}
+
     # ---- alpha sweep (selection + attention only; stage 1 does not depend on alpha) --
     sweep = []
     if not args.no_sweep and len(wl.alphas) > 1:
@@ -284,8 +302,32 @@ def main() -> int:
                 "mean_k_c": float(cca.mean()), "mean_k_s": float(sca.mean()),
                 "speedup_vs_dense": (dense_ms / total) if dense_ms else None,
                 "flash_tflops": float(tl.sum()) * TILE_FLOP / (t_fl * 1e-3) / 1e12,
+                **(recall_stats(plan.lse) if plan.lse is not None else {}),
             })
             log(f"alpha {a}: {json.dumps(sweep[-1])}")
+
+    # ---- separate thresholds for columns and slashes (Sec. 4.1: alpha decomposed) -----
+    grid = []
+    if args.alpha_grid:
+        plan.sample(q, k)
+        for ac in (0.8, 0.9, 0.95):
+            for as_ in (0.8, 0.9, 0.95):
+                plan.select(ac, as_)
+                plan.attend(q, k, v, w)          # warm
+                torch.cuda.synchronize()
+                sa.sa_profile_enable(True)
+                plan.select(ac, as_)
+                plan.attend(q, k, v, w)
+                torch.cuda.synchronize()
+                t_fl = float(np.mean(sa.sa_profile_read("sparse_flash")))
+                tl = plan.tiles.cpu().numpy().astype(np.int64)
+                grid.append({
+                    "alpha_c": ac, "alpha_s": as_, "sparse_flash_ms": t_fl,
+                    "computed_tile_fraction": float(tl.sum()) / dense_tiles,
+                    "mean_k_c": float(plan.col_cnt.float().mean()), "mean_k_s": float(plan.slash_cnt.float().mean()),
+                    **(recall_stats(plan.lse) if plan.lse is not None else {}),
+                })
+                log(f"grid: {json.dumps(grid[-1])}")
     # ---- the same workload at block granularity (Algorithm 1 with blk = 128): with the
     #      workload's sampled rows, and with the paper's 128 sampled rows -----------------
     block_runs = []
@@ -296,6 +338,7 @@ def main() -> int:
             variants.append((128, 2))         # Algorithm 1 as printed: chunk_n = 2, 128 rows per chunk
         for bn_s, n_chunks in variants:
             bplan = sa.SampleAttentionPlan(shape, bn_s, granularity=blk, n_chunks=n_chunks)
+            bplan.lse = plan.lse
             for a in wl.alphas:
                 bplan.run(q, k, v, a, a, w)          # warm
                 torch.cuda.synchronize()
@@ -319,6 +362,7 @@ def main() -> int:
                     "mean_k_c_blocks": float(cca.mean()), "mean_k_s_blocks": float(sca.mean()),
                     "speedup_vs_dense": (dense_ms / total) if dense_ms else None,
                     "flash_tflops": float(tl.sum()) * TILE_FLOP / (t["sparse_flash"] * 1e-3) / 1e12,
+                    **(recall_stats(bplan.lse) if bplan.lse is not None else {}),
                 })
                 log(f"block: {json.dumps(block_runs[-1])}")
             del bplan
@@ -375,6 +419,7 @@ def main() -> int:
         "speedup_vs_dense": (dense_ms / ms_per_step) if dense_ms else None,
         "alpha_sweep": sweep,
         "block_granularity_runs": block_runs,
+        "alpha_c_alpha_s_grid": grid,
     }
     print(json.dumps(line), flush=True)
     return 0

@@ -402,7 +402,7 @@ class SampleAttentionPlan:
     and nothing else (no allocation, no host synchronisation)."""
 
     def __init__(self, shape: Shape, n_sample_rows: int, device="cuda", out_dtype: int = SA_OUT_BF16,
-                 granularity: int = 1, n_chunks: int = 1):
+                 granularity: int = 1, n_chunks: int = 1, with_lse: bool = False):
         lib = load_library()
         self.lib, self.shape, self.n_s, self.out_dtype = lib, shape, n_sample_rows, out_dtype
         self.granularity, self.n_chunks = granularity, n_chunks
@@ -424,6 +424,8 @@ class SampleAttentionPlan:
         self.col_cnt = torch.empty(*lead, n, dtype=torch.int32, device=device)
         self.slash_cnt = torch.empty_like(self.col_cnt)
         self.tiles = torch.zeros(n, dtype=torch.int64, device=device)
+        # optional log-sum-exp of every row, as the attention calls write it (masked or dense)
+        self.lse = torch.empty(n, shape.seq_len, dtype=torch.float32, device=device) if with_lse else None
         odt = torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16
         self.out = torch.empty(shape.batch, shape.n_q_heads, shape.seq_len, shape.head_dim, dtype=odt, device=device)
 
@@ -459,7 +461,7 @@ class SampleAttentionPlan:
             self._ok(self.lib.sa_sparse_attn_chunked(ctypes.byref(self.cs), ctypes.byref(self.sm), _ptr(q), _ptr(k),
                                                      _ptr(v), _ptr(self.col_idx), _ptr(self.col_cnt),
                                                      _ptr(self.slash_idx), _ptr(self.slash_cnt), int(window),
-                                                     _ptr(self.out), self.out_dtype, None, _ptr(self.tiles),
+                                                     _ptr(self.out), self.out_dtype, _ptr(self.lse), _ptr(self.tiles),
                                                      _ptr(self.ws), self.ws.numel(), _stream()),
                      "sa_sparse_attn_chunked")
             return
@@ -467,17 +469,17 @@ class SampleAttentionPlan:
             self._ok(self.lib.sa_block_sparse_attn(ctypes.byref(self.cs), self.granularity, _ptr(q), _ptr(k), _ptr(v),
                                                    _ptr(self.col_idx), _ptr(self.col_cnt), _ptr(self.slash_idx),
                                                    _ptr(self.slash_cnt), int(window), _ptr(self.out),
-                                                   self.out_dtype, None, _ptr(self.tiles), _ptr(self.ws),
+                                                   self.out_dtype, _ptr(self.lse), _ptr(self.tiles), _ptr(self.ws),
                                                    self.ws.numel(), _stream()), "sa_block_sparse_attn")
             return
         self._ok(self.lib.sa_sparse_attn(ctypes.byref(self.cs), _ptr(q), _ptr(k), _ptr(v), _ptr(self.col_idx),
                                          _ptr(self.col_cnt), _ptr(self.slash_idx), _ptr(self.slash_cnt),
-                                         int(window), _ptr(self.out), self.out_dtype, None, _ptr(self.tiles),
+                                         int(window), _ptr(self.out), self.out_dtype, _ptr(self.lse), _ptr(self.tiles),
                                          _ptr(self.ws), self.ws.numel(), _stream()), "sa_sparse_attn")
 
     def dense(self, q, k, v):
         self._ok(self.lib.sa_dense_attn(ctypes.byref(self.cs), _ptr(q), _ptr(k), _ptr(v), _ptr(self.out),
-                                        self.out_dtype, None, _ptr(self.ws), self.ws.numel(), _stream()),
+                                        self.out_dtype, _ptr(self.lse), _ptr(self.ws), self.ws.numel(), _stream()),
                  "sa_dense_attn")
 
     def run(self, q, k, v, alpha_c, alpha_s, window):
