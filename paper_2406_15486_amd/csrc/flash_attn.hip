@@ -48,6 +48,10 @@ constexpr int OFF_V = OFF_K + NSTAGE * KTILE_B;
 constexpr int OFF_A = OFF_V + NSTAGE * VTILE_B;
 constexpr int OFF_DUMP = OFF_A + NAUX * AUX_B;      // 1 KB per wave: where loads of tiles past the end go
 constexpr int LDS_B = OFF_DUMP + 8 * 1024;          // 141312 bytes
+// The log-sum-exp sweep stages K only: its dump area follows the K stages, and with
+// 72 KB of LDS and at most 128 registers per lane two of its workgroups share a CU.
+constexpr int OFF_DUMP_LSE = OFF_V;
+constexpr int LDS_B_LSE = OFF_DUMP_LSE + 8 * 1024;  // 73728 bytes
 constexpr float kSumBound = 256.0f;    // a tile's exponentials may sum to 2^8 per lane before the reference maximum moves
 
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
@@ -100,9 +104,10 @@ __device__ __forceinline__ void wg_barrier() {
 
 // MODE: 0 dense causal, 1 row log-sum-exp only (no V), 2 strip-masked sparse.
 template <int MODE, bool OUT_F32>
-__global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
+__global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashParams P) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr bool WITH_V = (MODE != 1);
+  constexpr int kOffDump = WITH_V ? OFF_DUMP : OFF_DUMP_LSE;
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // 0..7, wave-uniform, kept in an SGPR
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     const uint32_t off = !real ? 0u : (col ? (uint32_t)t : (uint32_t)first_key(t, d)) * 2u;   // bytes into a V^T row; t * 64 keys for a gathered tile
     ld_vbase = col ? s_vct + (uint64_t)((uint32_t)t * (BK * 2u)) : s_vtbase + off;
     ld_vbase1 = ld_vbase + 128ull * (uint32_t)P.S_pad;            // run w + 8: 64 rows of V^T further on
-    ld_vdst = smem_lds + 1024 * wave + (real ? OFF_V + (t & (NSTAGE - 1)) * VTILE_B : OFF_DUMP);
+    ld_vdst = smem_lds + 1024 * wave + (real ? OFF_V + (t & (NSTAGE - 1)) * VTILE_B : kOffDump);
     ld_vstep = real ? 8192 : 0;                    // a stand-in tile writes both runs to the same dump kilobyte
   };
   auto load_k_begin = [&](int t, int d) {
@@ -290,7 +295,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
     const int row0 = min(!real ? 0 : (col ? t * BK : first_key(t, d)), kmax);
     ld_kbase = (col ? s_kc : s_kbase) + ((uint64_t)(uint32_t)row0 << 8);
     ld_klim = (uint32_t)(kmax - row0) * KROW_B + (koff0 & (KROW_B - 1));
-    ld_kdst = smem_lds + 1024 * wave + (real ? OFF_K + (t & (NSTAGE - 1)) * KTILE_B : OFF_DUMP);
+    ld_kdst = smem_lds + 1024 * wave + (real ? OFF_K + (t & (NSTAGE - 1)) * KTILE_B : kOffDump);
     ld_kstep = real ? 8192 : 0;
   };
   auto load_v_one = [&](int n) {
@@ -307,7 +312,7 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
   auto dma_aux = [&](int t, int d) {
     if (MODE != 2 || wave != (t & 7)) return;
     const bool real = t < n_tiles;
-    const uint32_t dst = smem_lds + (real ? OFF_A + (t & (NAUX - 1)) * AUX_B : OFF_DUMP);
+    const uint32_t dst = smem_lds + (real ? OFF_A + (t & (NAUX - 1)) * AUX_B : kOffDump);
     if (real && is_col(t)) {
       dma4(s_cidx + (uint64_t)((uint32_t)t * (BK * 4u)), 4u * lane, dst);
     } else {
@@ -613,7 +618,19 @@ __global__ __launch_bounds__(NT, 1) void flash_kernel(FlashParams P) {
       mm_pv((u - 1) & (NSTAGE - 1), u & (NSTAGE - 1), setup_a, setup_v, setup_k, look, decide);
     } else {
       ahead_setup();
-      if (pre_done) {
+      if (MODE == 1) {
+        // one call site for the warm-up: with two, the ring gets two homes in the
+        // log-sum-exp kernel and 32 register copies per tile (-6 % there; the other
+        // two kernels measured 1 % slower with this form, so they keep the one below)
+        if (pre_done) {
+          act_n = pre_act;
+        } else if (have) {
+          uint32_t aw0 = 0, aw1 = 0;
+          act_words(u, aw0, aw1);
+          act_n = tile_active(u, dq0, aw0, aw1);
+        }
+        if (act_n) warm_k(u & (NSTAGE - 1));
+      } else if (pre_done) {
         act_n = pre_act;
         if (act_n) warm_k(u & (NSTAGE - 1));
       } else if (have) {
@@ -726,17 +743,17 @@ hipError_t launch_lse_combine(const float* part, float* out, size_t n, int k, hi
 }
 
 // How many key splits even out the log-sum-exp launch: W workgroups of equal length cut
-// k ways take ceil(W k / 256) / k rounds on 256 CUs; a split keeps at least 64 tiles, and
+// k ways take ceil(W k / 512) / k rounds on 256 CUs x 2 workgroups; a split keeps at least 64 tiles, and
 // every row must see a key in every split (the sampled rows start at row_first).
 int lse_key_splits(int row_first, int n_s, int n_bh) {
   const int n_qtiles = (n_s + kFlashBQ - 1) / kFlashBQ;
   const long long W = (long long)n_qtiles * n_bh;
   const int min_tiles = row_first / kFlashBK;       // key tiles the first sampled row sees, at least
   int best = 1;
-  double best_t = (double)((W + 255) / 256);
+  double best_t = (double)((W + 511) / 512);
   for (int k = 2; k <= 8; k *= 2) {
     if (min_tiles / k < 64) break;
-    double t = (double)((W * k + 255) / 256) / k;
+    double t = (double)((W * k + 511) / 512) / k;
     if (t < best_t - 1e-9) { best_t = t; best = k; }
   }
   return best;
@@ -744,7 +761,7 @@ int lse_key_splits(int row_first, int n_s, int n_bh) {
 
 template <int MODE, bool OUT_F32>
 static hipError_t launch_one(const FlashParams& P, int grid, hipStream_t st) {
-  size_t shmem = LDS_B;
+  size_t shmem = (MODE == 1) ? LDS_B_LSE : LDS_B;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kernel<MODE, OUT_F32>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return e;
