@@ -17,12 +17,14 @@
 // w and w+4 share a SIMD.  Left alone, two waves that alternate an MFMA section
 // and a vector-ALU (softmax) section fall into step - both on the matrix pipe,
 // then both on the vector pipe - and each pipe idles half the time.  Here the
-// groups are held one phase apart by two workgroup barriers per tile: while group
-// 0 does the softmax of tile t, group 1 issues the MFMAs of P V(t-1) and
-// K Q^T(t), and vice versa, so every SIMD always has one wave feeding the matrix
-// pipe and one feeding the vector pipe.  Both groups read the same K/V tiles,
-// which therefore stay in LDS for two phases; four stages of each are resident,
-// filled by direct global->LDS loads two and three tiles ahead.
+// groups run the two phases of a tile in opposite order - group 0 the MFMAs of
+// P V(t-1) and K Q^T(t) and then the softmax of tile t, group 1 the softmax of
+// tile t-1 and then the same MFMAs - and one workgroup barrier per tile re-aligns
+// them, so every SIMD always has one wave feeding the matrix pipe and one feeding
+// the vector pipe.  Both groups read the same K/V tiles; four stages of each are
+// resident in LDS, filled by direct global->LDS loads two and three tiles ahead.
+// The log-sum-exp sweep stages no V and needs half the registers: two of its
+// workgroups share a CU.
 #include "sa_device.h"
 #include "sa_kernels.h"
 
