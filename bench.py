@@ -147,6 +147,60 @@ def cpu_baseline(wl, x, alpha: float, budget_s: float) -> dict:
     }
 
 
+def sampling_study(sa, torch, wl, q, k, v, shape) -> int:
+    """How much recall does sampling cost?  (Appendix "effectiveness of sampling": CRA
+    reached by top-k strips chosen from a few sampled rows against top-k strips chosen
+    from the full attention matrix, at equal k.)  Strip budgets are fractions of S for
+    columns and offsets alike; the scores come from sa_sample_scores (all rows = n_s =
+    S), the top-k lists from torch.topk (harness code, not part of the path), the
+    recall from the log-sum-exps of sa_sparse_attn and sa_dense_attn."""
+    S, Hq, w = wl.seq_len, wl.n_q_heads, wl.window
+    _, dense_lse = sa.sa_dense_attn(q, k, v, want_lse=True)
+    sources = [("all rows", S)] + [(f"last {n} rows", n) for n in sorted({128, wl.n_sample_rows}) if n < S]
+    rows = []
+    for name, n_s in sources:
+        col, slash = sa.sa_sample_scores(q, k, n_s)
+        for frac in (0.025, 0.05, 0.1, 0.2):
+            kk = max(1, int(round(frac * S)))
+            ci = torch.zeros(Hq, S, dtype=torch.int32, device="cuda")
+            si = torch.zeros_like(ci)
+            ci[:, :kk] = torch.topk(col, kk, dim=1).indices.sort(dim=1).values.int()
+            si[:, :kk] = torch.topk(slash, kk, dim=1).indices.sort(dim=1).values.int()
+            cnt = torch.full((Hq,), kk, dtype=torch.int32, device="cuda")
+            _, lse, tiles = sa.sa_sparse_attn(q, k, v, ci, cnt, si, cnt, w, want_lse=True, want_tiles=True)
+            torch.cuda.synchronize()
+            r = torch.exp(lse - dense_lse)
+            # the sampled rows are scored exactly; the question is how the mask does elsewhere
+            rows.append({"scores_from": name, "n_rows": n_s, "strip_fraction": frac, "k": kk,
+                         "recall_mean": float(r.mean()), "recall_p05": float(torch.quantile(r.flatten()[::7], 0.05)),
+                         "cra_min": float(r.min())})
+            log(f"sampling study: {json.dumps(rows[-1])}")
+        del col, slash
+    # the paper's remedy for bottom-only sampling: chunk_n segments, each masked by the strips its own
+    # bottom rows select (here at the same budgets, counted per segment)
+    for C in (4,):
+        if S % (256 * C) != 0:
+            continue
+        col, slash = sa.sa_sample_scores(q, k, 128, n_chunks=C)
+        for frac in (0.025, 0.05, 0.1, 0.2):
+            kk = max(1, int(round(frac * S)))
+            ci = torch.zeros(C, Hq, S, dtype=torch.int32, device="cuda")
+            si = torch.zeros_like(ci)
+            ci[:, :, :kk] = torch.topk(col, kk, dim=2).indices.sort(dim=2).values.int()
+            si[:, :, :kk] = torch.topk(slash, kk, dim=2).indices.sort(dim=2).values.int()
+            cnt = torch.full((C, Hq), kk, dtype=torch.int32, device="cuda")
+            _, lse, _ = sa.sa_sparse_attn_chunked(q, k, v, ci, cnt, si, cnt, w, C, want_lse=True)
+            torch.cuda.synchronize()
+            r = torch.exp(lse - dense_lse)
+            rows.append({"scores_from": f"last 128 rows of each of {C} segments", "n_rows": 128 * C,
+                         "strip_fraction": frac, "k": kk, "recall_mean": float(r.mean()),
+                         "recall_p05": float(torch.quantile(r.flatten()[::7], 0.05)), "cra_min": float(r.min())})
+            log(f"sampling study: {json.dumps(rows[-1])}")
+    print(json.dumps({"study": "sampled vs full scores at equal strip budgets", "workload": wl.name,
+                      "seq_len": S, "window": w, "rows": rows}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -163,6 +217,9 @@ def main() -> int:
     ap.add_argument("--no-block", action="store_true", help="skip the block-granularity runs")
     ap.add_argument("--alpha-grid", action="store_true",
                     help="also run a grid of separate column / slash thresholds (alpha_c x alpha_s)")
+    ap.add_argument("--sampling-study", action="store_true",
+                    help="compare masks chosen from sampled scores with masks chosen from the scores of ALL rows "
+                         "at equal strip budgets (recall of the dense softmax), then exit")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (calibrates HBM byte counters)")
     ap.add_argument("--cpu-seconds", type=float, default=8.0,
@@ -195,6 +252,9 @@ def main() -> int:
     shape = sa.Shape(1, Hq, Hkv, S)
     plan = sa.SampleAttentionPlan(shape, n_s)
     torch.cuda.synchronize()
+
+    if args.sampling_study:
+        return sampling_study(sa, torch, wl, q, k, v, shape)
 
     if args.copy_calib_mib > 0:
         # a plain copy of known size: what FETCH_SIZE / WRITE_SIZE read for it scales the counters
