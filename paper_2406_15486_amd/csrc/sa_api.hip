@@ -322,10 +322,9 @@ sa_status select_both(const sa_shape* shape, int n_chunks, int granularity,
   sa::SelectParams P;
   P.n_prob = n_chunks * d.n_bh;   // every (chunk, head) is a problem of its own
   P.S = (d.S + granularity - 1) / granularity;
+  // both directions in one launch: twice the workgroups on an otherwise mostly idle chip
   P.scores = col_scores; P.idx = col_idx; P.cnt = col_cnt; P.alpha = alpha_c;
-  s = dev(sa::launch_select(P, st));
-  if (s != SA_OK) return s;
-  P.scores = slash_scores; P.idx = slash_idx; P.cnt = slash_cnt; P.alpha = alpha_s;
+  P.scores2 = slash_scores; P.idx2 = slash_idx; P.cnt2 = slash_cnt; P.alpha2 = alpha_s;
   return dev(sa::launch_select(P, st));
 }
 }  // namespace

@@ -102,6 +102,8 @@ struct SelectParams {
   int32_t* cnt;             // [n_prob]
   int n_prob, S;
   float alpha;
+  // optional second set of n_prob problems of the same size, solved by the same launch
+  const float* scores2; int32_t* idx2; int32_t* cnt2; float alpha2;
 };
 hipError_t launch_select(const SelectParams& P, hipStream_t st);
 

@@ -28,16 +28,20 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
   __shared__ unsigned int wtie[NW], wsel[NW];
   __shared__ unsigned int tie_base, sel_base;
 
-  const int prob = blockIdx.x;
+  // workgroups [0, n_prob) take the first set of problems, [n_prob, 2 n_prob) the
+  // second one (the two directions of a layer in one launch)
+  const bool second = (int)blockIdx.x >= P.n_prob;
+  const int prob = second ? (int)blockIdx.x - P.n_prob : (int)blockIdx.x;
   const int S = P.S;
-  const float* sc = P.scores + (size_t)prob * S;
-  int32_t* idx = P.idx + (size_t)prob * S;
+  const float* sc = (second ? P.scores2 : P.scores) + (size_t)prob * S;
+  int32_t* idx = (second ? P.idx2 : P.idx) + (size_t)prob * S;
+  int32_t* cnt_out = (second ? P.cnt2 : P.cnt) + prob;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const double alpha = (double)P.alpha;
+  const double alpha = (double)(second ? P.alpha2 : P.alpha);
 
   if (alpha >= 1.0) {                       // keep everything
     for (int i = tid; i < S; i += NT) idx[i] = i;
-    if (tid == 0) P.cnt[prob] = S;
+    if (tid == 0) *cnt_out = S;
     return;
   }
 
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
     mask |= 255u << shift;
     __syncthreads();
     if (sh_done) {
-      if (tid == 0) P.cnt[prob] = 0;
+      if (tid == 0) *cnt_out = 0;
       return;
     }
   }
@@ -139,14 +143,15 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
     }
     __syncthreads();
   }
-  if (tid == 0) P.cnt[prob] = (int)sel_base;
+  if (tid == 0) *cnt_out = (int)sel_base;
 }
 
 }  // namespace
 
 hipError_t launch_select(const SelectParams& P, hipStream_t st) {
   if (P.n_prob <= 0) return hipSuccess;
-  hipLaunchKernelGGL(select_kernel, dim3(P.n_prob), dim3(NT), 0, st, P);
+  const int sets = (P.scores2 != nullptr) ? 2 : 1;
+  hipLaunchKernelGGL(select_kernel, dim3(sets * P.n_prob), dim3(NT), 0, st, P);
   return hipGetLastError();
 }
 
