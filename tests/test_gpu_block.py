@@ -134,10 +134,11 @@ def _block_case(x, Ic, Is, w, blk, what, f32_out=False):
 
 
 @pytest.mark.parametrize("S,Hq,Hkv,w,blk", [(1024, 1, 1, 64, 128), (1500, 4, 2, 128, 128), (1300, 2, 2, 1, 64),
-                                            (2000, 2, 1, 300, 256), (300, 2, 2, 1, 128), (100, 1, 1, 5, 128)])
+                                            (2000, 2, 1, 300, 256), (300, 2, 2, 1, 128), (100, 1, 1, 5, 128),
+                                            (1, 1, 1, 1, 128), (64, 2, 1, 500, 64), (257, 1, 1, 2, 256)])
 def test_block_sparse_attn_random_blocks(S, Hq, Hkv, w, blk):
     _say(f"block sparse random S={S} Hq={Hq} w={w} blk={blk}")
-    wl, x = _inputs("glm8k", S, Hq, Hkv, n_sinks=8)
+    wl, x = _inputs("glm8k", S, Hq, Hkv, n_sinks=min(8, S))
     nb = (S + blk - 1) // blk
     rng = np.random.default_rng(S + w + blk)
     Ic = [np.sort(rng.choice(nb, rng.integers(0, nb // 3 + 1), replace=False)) for _ in range(Hq)]
