@@ -5,7 +5,7 @@ One *step* = one pass of the whole path over one layer's attention inputs:
 sa_sample_scores -> sa_select_strips -> sa_sparse_attn, chained on one stream
 with the inputs already resident in HBM.  Prints ONE JSON line:
 
-  metric  sparse prefill attention ms/layer (the benchmark's metric) on the
+  metric  sparse prefill attention ms/layer (the headline metric) on the
           workload named in config.workload (default: the S=128K ChatGLM3-6B-
           shaped config, alpha = 0.95, literal generator constants)
   roofline      the strip-masked flash kernel against the bf16 MFMA peak:
@@ -16,7 +16,10 @@ with the inputs already resident in HBM.  Prints ONE JSON line:
                 same workload, extrapolated linearly to one layer
 
 Everything else on the line (per-stage times, the in-library dense kernel,
-speedup, kept fractions, alpha sweep) is context.
+speedup, kept fractions, alpha sweep with the recall of each mask, the same
+workload at block granularity and with two chunks) is context.  --alpha-grid
+adds separate column / slash thresholds; --sampling-study replaces the run by
+a comparison of sampled against full scores.
 """
 from __future__ import annotations
 
