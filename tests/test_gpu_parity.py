@@ -270,3 +270,34 @@ def test_pipeline_end_to_end(name, S, Hq, Hkv, gain):
                 assert gap < 1e-3, (nm, h, gap)
         want_out, _ = O.masked_attn(qf[h], kf[h // G], vf[h // G], gc, gs, w)
         _check_out(out[0, h].float().cpu().numpy(), want_out, f"pipeline out h{h}")
+
+
+# ------------------------------------------------------------------- batch ----
+@pytest.mark.parametrize("blk", [1, 128])
+def test_batch_of_two_sequences(blk):
+    """[batch, heads, seq, d] with batch = 2: every (batch, head) pair is an
+    independent problem and query head h of batch b reads KV head h // group of
+    the same batch.  Compared with the same calls on each sequence alone."""
+    import paper_2406_15486_amd as sa
+    _say(f"batch 2, blk={blk}")
+    S, Hq, Hkv, n_s, w, alpha = 1300, 4, 2, 64, 32, 0.9
+    xs = [_inputs("glm8k", S=S, Hq=Hq, Hkv=Hkv, seed=s, n_sinks=8)[1] for s in (11, 12)]
+    q = torch.cat([_dev(x["q"]) for x in xs]).contiguous()
+    k = torch.cat([_dev(x["k"]) for x in xs]).contiguous()
+    v = torch.cat([_dev(x["v"]) for x in xs]).contiguous()
+    if blk == 1:
+        out = sa.sample_attention(q, k, v, n_s, alpha, alpha, w)
+        ones = [sa.sample_attention(q[b:b + 1].contiguous(), k[b:b + 1].contiguous(), v[b:b + 1].contiguous(),
+                                    n_s, alpha, alpha, w) for b in range(2)]
+    else:
+        out = sa.block_sample_attention(q, k, v, n_s, alpha, alpha, w, blk)
+        ones = [sa.block_sample_attention(q[b:b + 1].contiguous(), k[b:b + 1].contiguous(),
+                                          v[b:b + 1].contiguous(), n_s, alpha, alpha, w, blk) for b in range(2)]
+    dense, _ = sa.sa_dense_attn(q, k, v)
+    torch.cuda.synchronize()
+    for b in range(2):
+        assert torch.equal(out[b], ones[b][0]), f"batch element {b} differs from the single-sequence call"
+    # and against the oracle: the dense kernel on the second sequence, one head of its second KV group
+    x = xs[1]
+    want, _ = O.dense_attn(_f64(x["q"])[3], _f64(x["k"])[1], _f64(x["v"])[1])
+    _check_out(dense[1, 3].float().cpu().numpy(), want, "batch dense b1 h3")
