@@ -301,3 +301,51 @@ def test_batch_of_two_sequences(blk):
     x = xs[1]
     want, _ = O.dense_attn(_f64(x["q"])[3], _f64(x["k"])[1], _f64(x["v"])[1])
     _check_out(dense[1, 3].float().cpu().numpy(), want, "batch dense b1 h3")
+
+
+# ---------------------------------------------------------------- numerics ----
+def _bf16_bits(a):
+    """float array -> bf16 bit patterns (round to nearest even), as the generator does."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+@pytest.mark.parametrize("kind", ["rising", "falling", "spiky"])
+def test_large_logits_exercise_the_reference_maximum(kind):
+    """Scores far from N(0,1): a maximum that rises with every key tile (the
+    accumulators are rescaled again and again), one that is met in the first tile
+    and never again, and isolated keys 40 logits above the rest.  Dense and
+    strip-masked kernels against the oracle."""
+    import paper_2406_15486_amd as sa
+    _say(f"large logits: {kind}")
+    S, d = 1500, 128
+    rng = np.random.default_rng(5)
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    q = rng.standard_normal((1, S, d)) + 6.0 * u
+    k = rng.standard_normal((1, S, d))
+    v = rng.standard_normal((1, S, d))
+    ramp = np.arange(S)[:, None] / S
+    if kind == "rising":
+        k += 60.0 * ramp * u            # logit grows by ~32 over the sequence
+    elif kind == "falling":
+        k += 60.0 * (1.0 - ramp) * u
+    else:
+        k[0, rng.choice(S, 12, replace=False)] += 75.0 * u
+    x = {"q": _bf16_bits(q), "k": _bf16_bits(k), "v": _bf16_bits(v)}
+    qd, kd, vd = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    dense, dlse = sa.sa_dense_attn(qd, kd, vd, out_dtype=sa.SA_OUT_F32, want_lse=True)
+    torch.cuda.synchronize()
+    qf, kf, vf = _f64(x["q"])[0], _f64(x["k"])[0], _f64(x["v"])[0]
+    want, wlse = O.dense_attn(qf, kf, vf)
+    _check_out(dense[0, 0].cpu().numpy(), want, f"dense {kind}")
+    assert np.abs(dlse[0].cpu().numpy() - wlse).max() < 2e-3 * max(1.0, np.abs(wlse).max() / 10)
+    Ic = [np.sort(rng.choice(S, 300, replace=False))]
+    Is = [np.sort(rng.choice(S, 200, replace=False))]
+    _sparse_case(None, x, Ic, Is, 16, f"sparse {kind}", f32_out=True)
+    # stage 1 on the same inputs: the probabilities are recomputed from the row log-sum-exps
+    col, slash = sa.sa_sample_scores(qd, kd, 192)
+    torch.cuda.synchronize()
+    wc, ws, _ = O.sample_scores(qf, kf, 192)
+    _score_tol(col[0].cpu().numpy(), wc, f"col {kind}")
+    _score_tol(slash[0].cpu().numpy(), ws, f"slash {kind}")
