@@ -349,3 +349,59 @@ def test_large_logits_exercise_the_reference_maximum(kind):
     wc, ws, _ = O.sample_scores(qf, kf, 192)
     _score_tol(col[0].cpu().numpy(), wc, f"col {kind}")
     _score_tol(slash[0].cpu().numpy(), ws, f"slash {kind}")
+
+
+# ----------------------------------------------------------------- boundary ----
+def test_side_stream_and_repeatability():
+    """The library enqueues on the stream it is given and nothing else: the whole
+    path on a side stream gives the bits of the default-stream run, and so does a
+    second run (no atomics on floating point anywhere in the path)."""
+    import paper_2406_15486_amd as sa
+    _say("side stream / repeatability")
+    wl, x = _inputs("glm32k", S=3000, Hq=4, Hkv=2)
+    q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    args = (wl.n_sample_rows // 64 * 64 or 64, 0.95, 0.9, wl.window)
+    a = sa.sample_attention(q, k, v, *args)
+    b = sa.sample_attention(q, k, v, *args)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        c = sa.sample_attention(q, k, v, *args)
+        d = sa.block_sample_attention(q, k, v, 128, 0.95, 0.9, wl.window, 128)
+    side.synchronize()
+    e = sa.block_sample_attention(q, k, v, 128, 0.95, 0.9, wl.window, 128)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b), "two runs differ"
+    assert torch.equal(a, c), "side-stream run differs"
+    assert torch.equal(d, e), "block path: side-stream run differs"
+
+
+def test_sparse_attn_explicit_scale_and_shared_workspace():
+    """softmax_scale other than 1/sqrt(d), and one caller-owned workspace reused by
+    consecutive calls of different entry points."""
+    import paper_2406_15486_amd as sa
+    _say("explicit scale, shared workspace")
+    S, Hq = 1100, 2
+    wl, x = _inputs("glm8k", S=S, Hq=Hq, Hkv=1, n_sinks=8)
+    q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    sh = sa.Shape(1, Hq, 1, S, softmax_scale=0.05)
+    need = max(sa.sa_workspace_bytes(op, sh, 64) for op in (0, 2, 3))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    col, slash = sa.sa_sample_scores(q, k, 64, scale=0.05, workspace=ws)
+    ci, cc, si, sc = sa.sa_select_strips(col, slash, 0.9, 0.9, sh)
+    out, lse, _ = sa.sa_sparse_attn(q, k, v, ci, cc, si, sc, 8, scale=0.05, workspace=ws, want_lse=True,
+                                    out_dtype=sa.SA_OUT_F32)
+    dense, _ = sa.sa_dense_attn(q, k, v, scale=0.05, workspace=ws, out_dtype=sa.SA_OUT_F32)
+    torch.cuda.synchronize()
+    s32 = float(np.float32(0.05))
+    qf, kf, vf = _f64(x["q"]), _f64(x["k"])[0], _f64(x["v"])[0]
+    for h in range(Hq):
+        wc, wsl, _ = O.sample_scores(qf[h], kf, 64, scale=s32)
+        _score_tol(col[h].cpu().numpy(), wc, f"col scale h{h}")
+        gc, gs = ci[h, :int(cc[h])].cpu().numpy(), si[h, :int(sc[h])].cpu().numpy()
+        want, wlse = O.masked_attn(qf[h], kf, vf, gc, gs, 8, scale=s32)
+        _check_out(out[0, h].cpu().numpy(), want, f"sparse scale h{h}")
+        assert np.abs(lse[h].cpu().numpy() - wlse).max() < 2e-3
+        wd, _ = O.dense_attn(qf[h], kf, vf, scale=s32)
+        _check_out(dense[0, h].cpu().numpy(), wd, f"dense scale h{h}")
