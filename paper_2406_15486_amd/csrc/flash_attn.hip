@@ -543,7 +543,10 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     };
     exponentials();
     if (__any(!(rs <= kSumBound))) {
+      // (the maximum starts from a value the compiler cannot see through: otherwise it
+      // forms the whole maximum ahead of the branch, on every tile)
       float mx = s[0][0];
+      asm volatile("" : "+v"(mx));
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
