@@ -25,6 +25,8 @@
 // resident in LDS, filled by direct global->LDS loads two and three tiles ahead.
 // The log-sum-exp sweep stages no V and needs half the registers: two of its
 // workgroups share a CU.
+#include <type_traits>
+
 #include "sa_device.h"
 #include "sa_kernels.h"
 
@@ -109,6 +111,11 @@ template <int MODE, bool OUT_F32>
 __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashParams P) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr bool WITH_V = (MODE != 1);
+  // Where a wave issues its share of the tile loads.  Each direct load stalls the wave
+  // 40-100 cycles; the two MFMA phases of a SIMD hardly overlap, so a stall there costs
+  // the iteration, while the softmax phase is the shorter one and has room.  The
+  // log-sum-exp sweep is the other way round (short MFMA phase, no P V).
+  constexpr bool kLoadsInSoftmax = (MODE != 1);
   constexpr int kOffDump = WITH_V ? OFF_DUMP : OFF_DUMP_LSE;
 
   const int tid = threadIdx.x;
@@ -272,8 +279,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     voff0 = (uint32_t)d * (uint32_t)P.S_pad * 2u + cv * 16;
   }
   // The loads are issued one at a time (load_v_one / load_k_one, n = 0, 1), so the
-  // caller can spread them between its MFMAs: a wave that issues them back to back
-  // stalls on each.  Loads of a tile past the end of the schedule still go out (to a
+  // caller can spread them between its exponentials (or its MFMAs): a wave that issues
+  // them back to back stalls on each.  Loads of a tile past the end of the schedule still go out (to a
   // stand-in address and the wave's dump area), which keeps the number of loads per
   // phase, and with it the vmcnt arithmetic, constant.
   uint64_t ld_vbase = 0, ld_vbase1 = 0, ld_kbase = 0;
@@ -397,15 +404,17 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       // scalar bookkeeping in small pieces, so that no gap between two MFMAs grows long
-      if (i == 1) setup_a();
-      if (i == 2) setup_v();
+      if (!kLoadsInSoftmax) {
+        if (i == 1) setup_a();
+        if (i == 2) setup_v();
+        if (i == 4) load_v_one(0);
+        if (i == 5) setup_k();
+        if (i == 7) load_v_one(1);
+        if (i == 10) load_k_one(0);
+        if (i == 13) load_k_one(1);
+      }
       if (i == 3) look();                          // read the words that say whether the next tile needs this wave
-      if (i == 4) load_v_one(0);
-      if (i == 5) setup_k();
-      if (i == 7) load_v_one(1);
       if (i == 9) decide();                        // ... and decide, under the MFMAs
-      if (i == 10) load_k_one(0);
-      if (i == 13) load_k_one(1);
       const int sb = i >> 3, u = (i >> 2) & 1, mb = i & 3;
       uint4 pw = {pk[sb][4 * u], pk[sb][4 * u + 1], pk[sb][4 * u + 2], pk[sb][4 * u + 3]};
       o[mb] = mfma_32x32x16(as_bf16x8(R[i & 7]), as_bf16x8(pw), o[mb]);      // O^T += V^T P^T
@@ -426,7 +435,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   auto mm_qk = [&](int bufq, bool with_loads) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      if (with_loads) {
+      if (with_loads && !kLoadsInSoftmax) {
         if (i == 2) load_v_one(0);
         if (i == 5) load_v_one(1);
         if (i == 8) load_k_one(0);
@@ -527,13 +536,20 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     // sum is large, inf or NaN) the row maximum of the tile is formed, the reference
     // moved up to it, the accumulators rescaled and the exponentials taken again.
     float rs = 0.f;
-    auto exponentials = [&]() {
+    auto exponentials = [&](auto first_tag) {
+      constexpr bool FIRST = decltype(first_tag)::value;
       rs = 0.f;
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
         float p[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
+          if (kLoadsInSoftmax && FIRST) {          // the loads of the tiles ahead, spread over the exponentials
+            if (sb == 0 && r == 4) load_v_one(0);
+            if (sb == 0 && r == 12) load_v_one(1);
+            if (sb == 1 && r == 4) load_k_one(0);
+            if (sb == 1 && r == 12) load_k_one(1);
+          }
           p[r] = fast_exp2(fmaf(s[sb][r], c2, -m_run));
           rs += p[r];
         }
@@ -541,7 +557,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
         for (int r = 0; r < 8; ++r) pk[sb][r] = pack_bf16x2(p[2 * r], p[2 * r + 1]);
       }
     };
-    exponentials();
+    exponentials(std::true_type{});
     if (__any(!(rs <= kSumBound))) {
       // (the maximum starts from a value the compiler cannot see through: otherwise it
       // forms the whole maximum ahead of the branch, on every tile)
@@ -563,21 +579,23 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
       }
-      exponentials();
+      exponentials(std::false_type{});
     }
     l_run += rs;
   };
 
   // ---- the two-phase pipeline --------------------------------------------------------
-  // MFMA phase(u):    P V(u-1), K Q^T(u); issue aux(u+3), V(u+2), K(u+3)
+  // MFMA phase(u):    P V(u-1), K Q^T(u)
   // softmax phase(u): softmax(u)
+  // Iteration u also issues the loads of aux(u+3), V(u+2), K(u+3): from its softmax phase
+  // (dense and strip-masked kernels) or from its MFMA phase (log-sum-exp sweep).
   // Group 0 runs MFMA phase u in the first half of iteration u, group 1 in the second.
   // Slot t % 4 of the K (V^T) ring is re-filled with tile t + 4 only after the barrier
   // that follows its last reader - K Q^T(t) (P V(t)) of group 1; a load is waited for
   // by the wave that issued it before the barrier that precedes its first reader.  Loads complete
   // in order, so "at most n in flight" means everything but the last n has landed: at
-  // the end of MFMA phase u the loads of phase u - 1 that feed the next softmax and
-  // K Q^T (V(u+1), and K(u+1) from phase u - 2) must be in, the rest may still fly.
+  // the end of iteration u the loads of iteration u - 1 that feed the next softmax and
+  // K Q^T (V(u+1), and K(u+1) from iteration u - 2) must be in, the rest may still fly.
   unsigned long long tiles_done = 0;
   bool act_t = false;                        // this wave has work on the tile whose softmax comes next
   bool pre_done = false, pre_act = false;    // the next tile was already looked at (and the ring warmed for it)
@@ -594,8 +612,15 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     for (int i = 0; i < 8; ++i) asm volatile("" : "=v"(pk[0][i]), "=v"(pk[1][i]));
   };
   auto forget_scores = [&]() { asm volatile("" : "=v"(s[0]), "=v"(s[1])); };
-  auto softmax_phase = [&](int u, int d_u, int d_next) {   // tile diagonals of tiles u and u + 1
+  auto softmax_phase = [&](int u, int d_u, int d_next, int it) {   // tile diagonals of tiles u and u + 1; iteration
     forget_ring_and_p();                     // consumed by the MFMA phase before
+    if (kLoadsInSoftmax) {
+      // the loads of iteration `it`: aux(it + 3), V(it + 2), K(it + 3)
+      dma_aux(it + 3, dq3);
+      load_v_begin(it + 2, dq2);
+      load_k_begin(it + 3, dq3);
+      if (!act_t) { load_v_one(0); load_v_one(1); load_k_one(0); load_k_one(1); }
+    }
     if (act_t) step_softmax(u, d_u);
     // A wave with nothing to do here looks at the next tile now, so that its next MFMA
     // phase knows at once whether it has work.
@@ -622,7 +647,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       auto decide = [&]() { act_n = have && tile_active(u, dq0, aw0, aw1); };
       mm_pv((u - 1) & (NSTAGE - 1), u & (NSTAGE - 1), setup_a, setup_v, setup_k, look, decide);
     } else {
-      ahead_setup();
+      if (!kLoadsInSoftmax) ahead_setup();
       if (MODE == 1) {
         // one call site for the warm-up: with two, the ring gets two homes in the
         // log-sum-exp kernel and 32 register copies per tile (-6 % there; the other
@@ -648,14 +673,19 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     pre_done = false;
     if (act_n) mm_qk(u & (NSTAGE - 1), !pv);
     __builtin_amdgcn_s_setprio(0);
-    if (!pv && !act_n) {
+    if (!kLoadsInSoftmax && !pv && !act_n) {
       load_v_one(0); load_v_one(1); load_k_one(0); load_k_one(1);
     }
     tiles_done += act_n ? 1 : 0;
     act_t = act_n;
     // everything but this phase's loads and the K loads of the one before has landed
     // (the wave that also fetched aux words waits for one load more than it must)
-    if (WITH_V) vm_wait<6>(); else vm_wait<4>();
+    if (!kLoadsInSoftmax) { if (WITH_V) vm_wait<6>(); else vm_wait<4>(); }
+  };
+  // before the barrier that ends an iteration everything has landed but that iteration's
+  // loads and the K loads of the one before
+  auto end_of_iteration_wait = [&]() {
+    if (kLoadsInSoftmax) { if (WITH_V) vm_wait<6>(); else vm_wait<4>(); }
   };
 #undef SA_PIN
 
@@ -685,7 +715,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       // for anywhere else, it would drain the LDS reads in flight as well
       const int dq4 = fetch_d(n + 4);
       mfma_phase(n);                         // n = 0: K Q^T(0) only; n = n_tiles: the last P V
-      softmax_phase(n, dq0, dq1);
+      softmax_phase(n, dq0, dq1, n);
+      end_of_iteration_wait();
       wg_barrier();
       dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
     }
@@ -693,8 +724,9 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     int dprev = 0;                           // tile diagonal of tile n - 1
     for (int n = 0; n <= n_tiles; ++n) {
       const int dq4 = fetch_d(n + 4);
-      softmax_phase(n - 1, dprev, dq0);
+      softmax_phase(n - 1, dprev, dq0, n);
       mfma_phase(n);
+      end_of_iteration_wait();
       wg_barrier();
       dprev = dq0; dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
     }
