@@ -305,6 +305,12 @@ def main() -> int:
         "select": 5 * sc_b + 4 * float(cc.sum() + sc.sum()),
     }
     stage_gbs = {n: stage_bytes[n] / (stage_ms[n] * 1e-3) / 1e9 for n in stage_bytes if stage_ms.get(n)}
+    # ... and against what actually bounds them: one QK^T contraction and one exponential per
+    # (sampled row, key <= row) pair in each of the two passes
+    pairs = float(Hq) * sum(min(i + 1, S) for i in range(S - n_s, S))
+    stage_compute = {n: {"mfma_tflops": 2.0 * 128 * pairs / (stage_ms[n] * 1e-3) / 1e12,
+                         "gexp_per_s": pairs / (stage_ms[n] * 1e-3) / 1e9}
+                     for n in ("row_lse", "score_accum") if stage_ms.get(n)}
 
     # ---- in-library dense kernel on the same inputs --------------------------------
     dense_ms = None
@@ -476,6 +482,7 @@ def main() -> int:
         "mask_density_head0": density0,
         "touched_128x128_block_fraction_head0": blocks0,
         "stage_hbm_gbs_algorithmic": stage_gbs,
+        "stage_compute": stage_compute,
         "mean_k_c": float(cc.mean()), "mean_k_s": float(sc.mean()),
         "dense_ms": dense_ms,
         "dense_kernel_tflops": dense_kernel_tflops if dense_ms else None,
