@@ -370,45 +370,17 @@ sa_status sa_select_chunked(const sa_shape* shape, const sa_sampling* sampling,
 }  // extern "C"
 
 namespace {
-// granularity 1: strip lists (per key / per offset); otherwise lists of blocks
-sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
-                      const void* q, const void* k, const void* v,
-                      const int32_t* col_idx_all, const int32_t* col_cnt_all,
-                      const int32_t* slash_idx_all, const int32_t* slash_cnt_all,
-                      int32_t local_window,
-                      void* out, int out_dtype, float* out_lse, uint64_t* tiles,
-                      void* workspace, size_t workspace_bytes, void* stream) {
-  Dims d;
-  sa_status s = check_shape(shape, &d);
-  if (s != SA_OK) return s;
-  s = check_chunks(d, n_chunks, granularity);
-  if (s != SA_OK) return s;
-  const bool blocks = granularity != 1;
-  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || col_idx_all == nullptr ||
-      col_cnt_all == nullptr || slash_idx_all == nullptr || slash_cnt_all == nullptr)
-    return SA_ERR_INVALID_ARG;
-  if (local_window < 1) return SA_ERR_INVALID_ARG;
-  if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
-  const BlockWs bw = block_ws(d, blocks ? granularity : 64);
+// One segment of the queries (query tiles [qtile0, qtile0 + n_qtiles)) under the mask
+// of one set of lists: metadata (merge_index), gathers, then the strip-masked kernel.
+// granularity 1: strip lists (per key / per offset); otherwise lists of blocks.
+sa_status attend_segment(const Dims& d, const BlockWs& bw, int granularity, bool first_segment,
+                         int qtile0, int n_qtiles, const void* q, const void* k, const void* v,
+                         const int32_t* col_idx, const int32_t* col_cnt,
+                         const int32_t* slash_idx, const int32_t* slash_cnt, int32_t local_window,
+                         void* out, int out_dtype, float* out_lse, uint64_t* tiles, char* ws, hipStream_t st) {
   const SparseWs& w = bw.sp;
-  s = check_ws(workspace, workspace_bytes, blocks ? bw.total : w.total);
-  if (s != SA_OK) return s;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
-  if (tiles != nullptr) {
-    s = dev(sa::launch_fill_u32(reinterpret_cast<uint32_t*>(tiles), 2 * (size_t)d.n_bh, 0u, st));
-    if (s != SA_OK) return s;
-  }
-  const size_t n_cand = (size_t)(d.S + granularity - 1) / granularity;   // list capacity per head
-  const int n_qtiles_all = (d.S + sa::kFlashBQ - 1) / sa::kFlashBQ;
-
-  // One pass per chunk: the strips selected from chunk m mask the query rows of
-  // segment m (merge_index with itv = S / chunk_n); a single chunk is the whole matrix.
-  for (int m = 0; m < n_chunks; ++m) {
-  const int32_t* col_idx = col_idx_all + (size_t)m * d.n_bh * n_cand;
-  const int32_t* slash_idx = slash_idx_all + (size_t)m * d.n_bh * n_cand;
-  const int32_t* col_cnt = col_cnt_all + (size_t)m * d.n_bh;
-  const int32_t* slash_cnt = slash_cnt_all + (size_t)m * d.n_bh;
+  const bool blocks = granularity != 1;
+  sa_status s = SA_OK;
   sa::MaskPrepParams M;
   {
     Scope sc(SA_K_MASK_PREP, st);
@@ -441,8 +413,8 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
     }
     if (s != SA_OK) return s;
 
-    // V^T for the contiguous (slash / window) tiles
-    if (m == 0) s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
+    // V^T for the contiguous (slash / window) tiles: once per call
+    if (first_segment) s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
     if (s != SA_OK) return s;
 
     // merge_index, column side: compact K rows and V^T columns of the kept keys, per query head
@@ -464,8 +436,8 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
     if (s != SA_OK) return s;
   }
   sa::FlashParams P = base_flash(d, q, k);
-  P.qtile0 = (int)((long long)n_qtiles_all * m / n_chunks);
-  P.n_qtiles = (int)((long long)n_qtiles_all * (m + 1) / n_chunks) - P.qtile0;
+  P.qtile0 = qtile0;
+  P.n_qtiles = n_qtiles;
   P.vt = reinterpret_cast<const uint16_t*>(ws + w.vt);
   P.out = out; P.lse = out_lse;
   P.kc = reinterpret_cast<const uint16_t*>(ws + w.kc);
@@ -478,8 +450,49 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
   P.cidx_stride = d.S_pad; P.cb_words = w.cb_words; P.rb_words = w.rb_words;
   P.dlist_stride = w.dlist_stride; P.off_max = w.off_max;
   Scope sc(SA_K_SPARSE_FLASH, st);
-  s = dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
+  return dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
+}
+
+// Argument checks, then one pass per chunk: the lists selected from chunk m mask the
+// query rows of segment m (merge_index with itv = S / chunk_n); a single chunk is the
+// whole matrix.
+sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
+                      const void* q, const void* k, const void* v,
+                      const int32_t* col_idx_all, const int32_t* col_cnt_all,
+                      const int32_t* slash_idx_all, const int32_t* slash_cnt_all,
+                      int32_t local_window,
+                      void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  Dims d;
+  sa_status s = check_shape(shape, &d);
   if (s != SA_OK) return s;
+  s = check_chunks(d, n_chunks, granularity);
+  if (s != SA_OK) return s;
+  const bool blocks = granularity != 1;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || col_idx_all == nullptr ||
+      col_cnt_all == nullptr || slash_idx_all == nullptr || slash_cnt_all == nullptr)
+    return SA_ERR_INVALID_ARG;
+  if (local_window < 1) return SA_ERR_INVALID_ARG;
+  if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
+  const BlockWs bw = block_ws(d, blocks ? granularity : 64);
+  s = check_ws(workspace, workspace_bytes, blocks ? bw.total : bw.sp.total);
+  if (s != SA_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  if (tiles != nullptr) {
+    s = dev(sa::launch_fill_u32(reinterpret_cast<uint32_t*>(tiles), 2 * (size_t)d.n_bh, 0u, st));
+    if (s != SA_OK) return s;
+  }
+  const size_t n_cand = (size_t)(d.S + granularity - 1) / granularity;   // list capacity per head
+  const int n_qtiles_all = (d.S + sa::kFlashBQ - 1) / sa::kFlashBQ;
+  for (int m = 0; m < n_chunks; ++m) {
+    const int qtile0 = (int)((long long)n_qtiles_all * m / n_chunks);
+    const int qtile1 = (int)((long long)n_qtiles_all * (m + 1) / n_chunks);
+    s = attend_segment(d, bw, granularity, m == 0, qtile0, qtile1 - qtile0, q, k, v,
+                       col_idx_all + (size_t)m * d.n_bh * n_cand, col_cnt_all + (size_t)m * d.n_bh,
+                       slash_idx_all + (size_t)m * d.n_bh * n_cand, slash_cnt_all + (size_t)m * d.n_bh,
+                       local_window, out, out_dtype, out_lse, tiles, ws, st);
+    if (s != SA_OK) return s;
   }
   return SA_OK;
 }
