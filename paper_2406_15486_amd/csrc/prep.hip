@@ -163,6 +163,21 @@ __global__ __launch_bounds__(256) void block_reduce_kernel(const float* in, floa
   if (lane == 0) out[(size_t)g * nb + b] = (float)acc;
 }
 
+// every offset 0 .. S-1 kept: bits off_max - (S-1) .. off_max of each head's bitmap
+__global__ void all_offsets_kernel(uint32_t* off_bits, int n_bh, int rb_words, int S, int off_max) {
+  const int x_lo = off_max - (S - 1), x_hi = off_max;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)n_bh * rb_words) return;
+  const int w = (int)(i % rb_words);
+  uint32_t m = 0u;
+  if (w >= (x_lo >> 5) && w <= (x_hi >> 5)) {
+    m = 0xFFFFFFFFu;
+    if (w == (x_lo >> 5)) m &= 0xFFFFFFFFu << (x_lo & 31);
+    if (w == (x_hi >> 5)) m &= 0xFFFFFFFFu >> (31 - (x_hi & 31));
+  }
+  off_bits[i] = m;
+}
+
 __device__ __forceinline__ int floor_div(int x, int y) { return x >= 0 ? x / y : -((-x + y - 1) / y); }
 
 // selected key blocks -> the token columns they hold (ascending, as the strip path
@@ -267,7 +282,8 @@ hipError_t launch_block_reduce(const float* in, float* out, int n_rows, int S, i
 hipError_t launch_block_prep(const BlockPrepParams& P, hipStream_t st) {
   size_t ncb = (size_t)P.n_bh * P.cb_words, nob = (size_t)P.n_bh * P.rb_words, ndb = (size_t)P.n_bh * P.db_words;
   hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, P.col_bits, ncb, 0u);
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, P.off_bits, nob, 0u);
+  hipLaunchKernelGGL(all_offsets_kernel, dim3((unsigned)((nob + 255) / 256)), dim3(256), 0, st, P.off_bits, P.n_bh,
+                     P.rb_words, P.S, P.off_max);
   hipLaunchKernelGGL(fill_u32_kernel, dim3(64), dim3(256), 0, st, P.diag_bits, ndb, 0u);
   dim3 grid((P.S + 255) / 256, P.n_bh);
   hipLaunchKernelGGL(expand_blocks_kernel, grid, dim3(256), 0, st, P);
@@ -275,7 +291,7 @@ hipError_t launch_block_prep(const BlockPrepParams& P, hipStream_t st) {
   MaskPrepParams M;
   M.col_idx = P.tok_idx; M.col_cnt = P.tok_cnt; M.slash_idx = nullptr; M.slash_cnt = nullptr;
   M.col_bits = P.col_bits; M.off_bits = P.off_bits; M.dlist = P.dlist; M.dcnt = P.dcnt;
-  M.n_bh = P.n_bh; M.S = P.S; M.window = P.S;   // offsets 0 .. S-1: all kept
+  M.n_bh = P.n_bh; M.S = P.S; M.window = 0;     // (the offset bitmap is already complete)
   M.cb_words = P.cb_words; M.rb_words = P.rb_words; M.dlist_stride = P.dlist_stride; M.off_max = P.off_max;
   hipLaunchKernelGGL(set_bits_kernel, grid, dim3(256), 0, st, M);
   hipLaunchKernelGGL(dlist_block_kernel, dim3(P.n_bh), dim3(256), 0, st, P);
