@@ -266,10 +266,12 @@ sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, con
  * Not thread-safe.
  */
 typedef enum {
-  SA_K_ROW_LSE = 0,        /* stage 1 pass 1: flash sweep giving row log-sum-exp   */
+  SA_K_ROW_LSE = 0,        /* stage 1 pass 1: flash sweep giving row log-sum-exp
+                              (and the combination of its key splits)              */
   SA_K_SCORE_ACCUM = 1,    /* stage 1 pass 2: column / slash accumulation          */
-  SA_K_SCORE_FINAL = 2,    /* stage 1: fixed-order sum of the partials             */
-  SA_K_SELECT = 3,         /* stage 2: both selection launches                     */
+  SA_K_SCORE_FINAL = 2,    /* stage 1: fixed-order sum of the partials, block
+                              reduction                                            */
+  SA_K_SELECT = 3,         /* stage 2: the selection launch (both directions)      */
   SA_K_MASK_PREP = 4,      /* merge: bitmaps, tile-diagonal list, V^T, K/V gathers */
   SA_K_SPARSE_FLASH = 5,   /* strip-masked flash attention kernel                  */
   SA_K_DENSE_FLASH = 6,    /* dense flash attention kernel                         */
