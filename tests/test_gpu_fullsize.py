@@ -4,6 +4,7 @@ cannot run these sizes end to end in seconds, so it is applied to sampled
 outputs it can compute one by one (single rows, single heads), plus properties
 that hold at any size (mass invariants, bit-exact selection on the GPU's own
 scores)."""
+import os
 import sys
 
 import numpy as np
@@ -195,3 +196,11 @@ def test_glm128k_two_chunks_block_granularity():
         _say(f"glm128k 2 chunks: out head {h}: max-abs {err.max():.3e} mean-abs {err.mean():.3e}")
         assert err.max() <= 2e-2 and err.mean() <= 2e-3
     assert (tiles.cpu().numpy() > 0).all()
+
+
+@pytest.mark.skipif(os.environ.get("SA_TEST_1M") != "1",
+                    reason="1M tokens: two minutes of host-side input generation; set SA_TEST_1M=1 (and run with -s)")
+def test_glm1m_long_config():
+    """The 1M-token configuration (2 % sampling): selection bit-exact on every head,
+    mass invariants, strip-masked and dense outputs on sampled rows of two heads."""
+    _run_full("glm1m", 0.95, score_heads=[], attn_heads=[2, 27], n_rows=48, lse_rows=8)
