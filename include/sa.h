@@ -135,10 +135,12 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
  * Stage 2 (Algorithm 1 "Score-Based Key-Value Block Filtering", Sec. 4.3).
  * Independently per head and per direction: order candidates by (score
  * descending, index ascending), take the smallest k >= 0 whose first-k score
- * sum (fp64) reaches alpha * total; alpha >= 1 keeps all seq_len candidates,
- * alpha == 0 keeps none.  Scores must be finite and >= 0.
+ * sum (fp64) reaches alpha * total; alpha == 1 keeps all seq_len candidates,
+ * alpha == 0 keeps none.  Scores are expected finite and >= 0; a negative,
+ * infinite or NaN score counts as 0 (it carries no mass and is kept last).
  * in:  col_scores, slash_scores  fp32 [batch*n_q_heads, seq_len]
- *      alpha_c, alpha_s          CRA thresholds, each >= 0
+ *      alpha_c, alpha_s          CRA thresholds in [0, 1] (SA_ERR_INVALID_ARG
+ *                                otherwise, NaN included)
  * out: col_idx, slash_idx  int32 [batch*n_q_heads, seq_len]; the first cnt[h]
  *                          entries of row h are the kept indices in ASCENDING
  *                          order, the rest is unspecified

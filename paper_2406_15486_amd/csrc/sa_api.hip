@@ -315,8 +315,8 @@ sa_status select_both(const sa_shape* shape, int n_chunks, int granularity,
   if (col_scores == nullptr || slash_scores == nullptr || col_idx == nullptr || col_cnt == nullptr ||
       slash_idx == nullptr || slash_cnt == nullptr)
     return SA_ERR_INVALID_ARG;
-  if (!(alpha_c >= 0.0f) || !(alpha_s >= 0.0f) || !isfinite(alpha_c) || !isfinite(alpha_s))
-    return SA_ERR_INVALID_ARG;
+  // the CRA thresholds of Algorithm 1 are fractions of the sampled mass
+  if (!(alpha_c >= 0.0f && alpha_c <= 1.0f) || !(alpha_s >= 0.0f && alpha_s <= 1.0f)) return SA_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
   Scope sc(SA_K_SELECT, st);
   sa::SelectParams P;

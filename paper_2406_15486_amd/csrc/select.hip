@@ -5,11 +5,26 @@
 // descending, index ascending) the kept set is {score > v} plus the first m
 // candidates with score == v, for the cut value v.  v is found by a most-
 // significant-digit radix descent over the fp32 bit patterns (non-negative
-// floats order like their bits): four passes of 8 bits, each building a
-// 256-bin histogram of (count, fp64 score sum) of the candidates that match
-// the digits fixed so far, then walking the bins from the top until the
-// running fp64 sum reaches the target.  A last pass writes the kept indices in
-// ascending order by stream compaction.  One workgroup per problem.
+// floats order like their bits): the exponent first, then the mantissa in
+// digits of 8, 8 and 7 bits.  Each pass builds a histogram, over the candidates
+// that match the digits fixed so far, of (count, sum of the 23-bit mantissas);
+// all candidates of a bin share their exponent, so the bin's score mass is
+// (count * 2^23 + mantissa sum) * 2^(e - 150) EXACTLY, from integer sums whose
+// order cannot matter.  One thread then walks the bins from the top, adding
+// their masses in fp64 in that fixed order, until the running sum reaches the
+// target.  Nothing in the kernel adds floating-point numbers atomically:
+// repeated runs give identical lists.
+//
+// The histogram lives in LDS and is updated with one 64-bit integer atomic per
+// candidate (count in the upper bits, mantissa sum below).  Scores of one head
+// crowd into a few exponents, and atomics of one wave to one address are served
+// one after the other; so every bin has kCopies copies, indexed by lane % kCopies
+// (then a wave's atomics land on distinct addresses and banks), which are added
+// up before the walk.
+//
+// A last double sweep writes the kept indices in ascending order: every wave owns
+// a contiguous segment of the candidates, counts what it will keep, and after one
+// exchange of the counts writes its part of the list.  One workgroup per problem.
 #include "sa_device.h"
 #include "sa_kernels.h"
 
@@ -19,14 +34,26 @@ namespace {
 
 constexpr int NT = 1024;
 constexpr int NW = NT / 64;
+constexpr int kCopies = 32;                 // copies of every histogram bin
+constexpr int kCntShift = 43;               // packed bin: count << 43 | mantissa sum (2^24 candidates at most:
+                                            // a copy sees 2^19 of them, mantissa sum < 2^42, count < 2^20)
+constexpr size_t kSelectLds = 256 * kCopies * sizeof(unsigned long long);
+
+// the bit pattern a score is ranked by: negative, infinite and NaN scores carry no
+// mass and rank with the zeros
+__device__ __forceinline__ unsigned int score_key(float v) {
+  const unsigned int u = __float_as_uint(v);
+  return (v > 0.0f && u < 0x7F800000u) ? u : 0u;
+}
 
 __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
-  __shared__ double hsum[256];
+  extern __shared__ __attribute__((aligned(16))) unsigned long long hist[];   // [256 bins][kCopies]
+  __shared__ unsigned long long hms[256];     // sum of the mantissas per bin
   __shared__ unsigned int hcnt[256];
+  __shared__ double bsum[256];                // mass per bin
   __shared__ double sh_above, sh_target;
-  __shared__ unsigned int sh_prefix, sh_above_cnt, sh_m, sh_done;
-  __shared__ unsigned int wtie[NW], wsel[NW];
-  __shared__ unsigned int tie_base, sel_base;
+  __shared__ unsigned int sh_prefix, sh_m, sh_done;
+  __shared__ unsigned int w_gt[NW], w_tie[NW];
 
   // workgroups [0, n_prob) take the first set of problems, [n_prob, 2 n_prob) the
   // second one (the two directions of a layer in one launch)
@@ -45,48 +72,68 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
     return;
   }
 
-  if (tid == 0) { sh_above = 0.0; sh_prefix = 0u; sh_above_cnt = 0u; sh_done = 0u; sh_m = 0u; }
-  unsigned int mask = 0u;
+  // every wave owns a contiguous run of whole 64-candidate groups
+  const int n_groups = (S + 63) / 64;
+  const int g_lo = (int)((long long)n_groups * wave / NW), g_hi = (int)((long long)n_groups * (wave + 1) / NW);
+
+  if (tid == 0) { sh_above = 0.0; sh_prefix = 0u; sh_done = 0u; sh_m = 0u; }
+  // digit p: bits [shift, shift + width) of the 31-bit key
   for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    if (tid < 256) { hsum[tid] = 0.0; hcnt[tid] = 0u; }
+    const int shift = (pass == 3) ? 0 : 23 - 8 * pass;
+    const int above_shift = (pass == 0) ? 31 : 31 - 8 * pass;    // bits from here up are fixed
+    const unsigned int dmask = (pass == 3) ? 127u : 255u;
+    for (int x = tid; x < 256 * kCopies; x += NT) hist[x] = 0ull;
     __syncthreads();
     const unsigned int prefix = sh_prefix;
-    for (int i = tid; i < S; i += NT) {
-      float v = sc[i];
-      unsigned int key = __float_as_uint(v) & 0x7FFFFFFFu;
-      if ((key & mask) == prefix) {
-        unsigned int b = (key >> shift) & 255u;
-        atomicAdd(&hcnt[b], 1u);
-        atomicAdd(&hsum[b], (double)__uint_as_float(key));
+    unsigned long long* my_hist = hist + (lane & (kCopies - 1));
+    for (int g = g_lo; g < g_hi; ++g) {
+      const int i = g * 64 + lane;
+      const unsigned int key = (i < S) ? score_key(sc[i]) : 0u;
+      const bool live = (i < S) && (pass == 0 || (key >> above_shift) == (prefix >> above_shift));
+      const unsigned int b = (key >> shift) & dmask;
+      if (live) atomicAdd(my_hist + b * kCopies, (1ull << kCntShift) | (unsigned long long)(key & 0x7FFFFFu));
+    }
+    __syncthreads();
+    if (tid < 256) {
+      // the copies of bin tid, each thread starting at another copy (spreads the LDS banks)
+      unsigned long long c = 0ull, ms = 0ull;
+      for (int x = 0; x < kCopies; ++x) {
+        const unsigned long long v = hist[tid * kCopies + ((x + tid) & (kCopies - 1))];
+        c += v >> kCntShift;
+        ms += v & ((1ull << kCntShift) - 1ull);
       }
+      hcnt[tid] = (unsigned int)c;
+      hms[tid] = ms;
+    }
+    __syncthreads();
+    if (tid < 256) {
+      // exponent of the bin's candidates: the bin itself in the first pass
+      const unsigned int e = (pass == 0) ? (unsigned int)tid : (prefix >> 23);
+      const unsigned long long units = (e > 0u ? ((unsigned long long)hcnt[tid] << 23) : 0ull) + hms[tid];
+      bsum[tid] = ldexp((double)units, e > 0u ? (int)e - 150 : -149);   // exact: units < 2^53
     }
     __syncthreads();
     if (tid == 0) {
       if (pass == 0) {
         double total = 0.0;
-        for (int b = 255; b >= 0; --b) total += hsum[b];
+        for (int b = 255; b >= 0; --b) total += bsum[b];
         sh_target = alpha * total;
         if (!(sh_target > 0.0)) sh_done = 1u;   // alpha == 0 or no mass: keep nothing
       }
       if (!sh_done) {
         double above = sh_above;
-        unsigned int acnt = sh_above_cnt;
         int chosen = -1, last_b = 0;
         double last_above = above;
-        unsigned int last_acnt = acnt;
-        for (int b = 255; b >= 0; --b) {
+        for (int b = (int)dmask; b >= 0; --b) {
           if (hcnt[b] == 0u) continue;
-          if (above + hsum[b] >= sh_target) { chosen = b; break; }
-          last_b = b; last_above = above; last_acnt = acnt;
-          above += hsum[b];
-          acnt += hcnt[b];
+          if (above + bsum[b] >= sh_target) { chosen = b; break; }
+          last_b = b; last_above = above;
+          above += bsum[b];
         }
-        if (chosen < 0) {   // only by fp64 rounding of the bin sums: cut inside the lowest non-empty bin
-          chosen = last_b; above = last_above; acnt = last_acnt;
+        if (chosen < 0) {   // only by fp64 rounding of the running sum: cut inside the lowest non-empty bin
+          chosen = last_b; above = last_above;
         }
         sh_above = above;
-        sh_above_cnt = acnt;
         sh_prefix = prefix | ((unsigned int)chosen << shift);
         if (pass == 3) {
           // all candidates left share the exact value v: how many are needed
@@ -103,7 +150,6 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
         }
       }
     }
-    mask |= 255u << shift;
     __syncthreads();
     if (sh_done) {
       if (tid == 0) *cnt_out = 0;
@@ -111,39 +157,40 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
     }
   }
 
+  // ---- ordered compaction: count per wave segment, exchange, write -------------
   const unsigned int vkey = sh_prefix;
   const unsigned int m = sh_m;
-  if (tid == 0) { tie_base = 0u; sel_base = 0u; }
-  __syncthreads();
-  for (int i0 = 0; i0 < S; i0 += NT) {
-    int i = i0 + tid;
-    unsigned int key = (i < S) ? (__float_as_uint(sc[i]) & 0x7FFFFFFFu) : 0u;
-    bool gt = (i < S) && key > vkey;
-    bool tie = (i < S) && key == vkey;
-    unsigned long long bt = __ballot(tie);
-    if (lane == 0) wtie[wave] = __popcll(bt);
-    __syncthreads();
-    unsigned int trank = tie_base;
-    for (int w = 0; w < wave; ++w) trank += wtie[w];
-    trank += __popcll(bt & ((1ull << lane) - 1ull));
-    bool sel = gt || (tie && trank < m);
-    unsigned long long bs = __ballot(sel);
-    if (lane == 0) wsel[wave] = __popcll(bs);
-    __syncthreads();
-    unsigned int pos = sel_base;
-    for (int w = 0; w < wave; ++w) pos += wsel[w];
-    pos += __popcll(bs & ((1ull << lane) - 1ull));
-    if (sel) idx[pos] = i;
-    __syncthreads();
-    if (tid == 0) {
-      unsigned int t = 0u, s = 0u;
-      for (int w = 0; w < NW; ++w) { t += wtie[w]; s += wsel[w]; }
-      tie_base += t;
-      sel_base += s;
-    }
-    __syncthreads();
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  unsigned int n_gt = 0u, n_tie = 0u;
+  for (int g = g_lo; g < g_hi; ++g) {
+    const int i = g * 64 + lane;
+    const unsigned int key = (i < S) ? score_key(sc[i]) : 0u;
+    n_gt += (unsigned int)__popcll(__ballot((i < S) && key > vkey));
+    n_tie += (unsigned int)__popcll(__ballot((i < S) && key == vkey));
   }
-  if (tid == 0) *cnt_out = (int)sel_base;
+  if (lane == 0) { w_gt[wave] = n_gt; w_tie[wave] = n_tie; }
+  __syncthreads();
+  unsigned int tie_run = 0u, pos_run = 0u;   // ties before this wave's segment; list position of its first kept index
+  for (int w = 0; w < wave; ++w) {
+    const unsigned int t = w_tie[w];
+    const unsigned int kept_ties = (tie_run >= m) ? 0u : ((m - tie_run < t) ? m - tie_run : t);
+    pos_run += w_gt[w] + kept_ties;
+    tie_run += t;
+  }
+  for (int g = g_lo; g < g_hi; ++g) {
+    const int i = g * 64 + lane;
+    const unsigned int key = (i < S) ? score_key(sc[i]) : 0u;
+    const bool gt = (i < S) && key > vkey;
+    const bool tie = (i < S) && key == vkey;
+    const unsigned long long bt = __ballot(tie);
+    const unsigned int trank = tie_run + (unsigned int)__popcll(bt & lt);
+    const bool sel = gt || (tie && trank < m);
+    const unsigned long long bs = __ballot(sel);
+    if (sel) idx[pos_run + (unsigned int)__popcll(bs & lt)] = i;
+    tie_run += (unsigned int)__popcll(bt);
+    pos_run += (unsigned int)__popcll(bs);
+  }
+  if (wave == NW - 1 && lane == 0) *cnt_out = (int)pos_run;
 }
 
 }  // namespace
@@ -151,7 +198,10 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
 hipError_t launch_select(const SelectParams& P, hipStream_t st) {
   if (P.n_prob <= 0) return hipSuccess;
   const int sets = (P.scores2 != nullptr) ? 2 : 1;
-  hipLaunchKernelGGL(select_kernel, dim3(sets * P.n_prob), dim3(NT), 0, st, P);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSelectLds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(select_kernel, dim3(sets * P.n_prob), dim3(NT), kSelectLds, st, P);
   return hipGetLastError();
 }
 

@@ -28,8 +28,11 @@ others.
 from __future__ import annotations
 
 import math
+import os
+import threading
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, replace
-from typing import Dict, Iterable, Optional, Sequence, Tuple
+from typing import Callable, Dict, Iterable, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -113,10 +116,20 @@ def rows_from_ratio(seq_len: int, ratio: float) -> int:
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round float32 to bf16 (nearest even); returns the uint16 bit patterns."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32)
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    r = u + np.uint32(0x7FFF) + lsb
-    return (r >> np.uint32(16)).astype(np.uint16)
+    u = x.reshape(-1).view(np.uint32)
+    out = np.empty(u.shape[0], dtype=np.uint16)
+    step = 1 << 18                      # cache-sized pieces: the temporaries stay small
+    t = np.empty(step, dtype=np.uint32)
+    for a in range(0, u.shape[0], step):
+        e = min(a + step, u.shape[0])
+        r = t[: e - a]
+        np.right_shift(u[a:e], np.uint32(16), out=r)
+        np.bitwise_and(r, np.uint32(1), out=r)
+        r += np.uint32(0x7FFF)
+        r += u[a:e]
+        np.right_shift(r, np.uint32(16), out=r)
+        out[a:e] = r
+    return out.reshape(x.shape)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -128,26 +141,70 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 # ----------------------------------------------------------------------------
 # rotary embedding
 # ----------------------------------------------------------------------------
-def _rope_inplace(x: np.ndarray, positions: np.ndarray, chunk: int = 1 << 15) -> None:
-    """Rotate rows of x ([n, d] float32) by their positions, in place."""
+class _RopeTable:
+    """cos / sin of ``pos * base**(-p/half)`` for pos = 0 .. n-1, formed in float64 and
+    rounded once to float32; rows are computed on first use and kept, so that the
+    many rotations of one workload (every head, every planted vector) share them."""
+
+    def __init__(self, half: int):
+        self.half = half
+        self.inv_freq = ROPE_BASE ** (-np.arange(half, dtype=np.float64) / half)
+        self.cos = np.zeros((0, half), dtype=np.float32)
+        self.sin = np.zeros((0, half), dtype=np.float32)
+        self.lock = threading.Lock()
+
+    def upto(self, n: int, chunk: int = 1 << 15):
+        with self.lock:
+            have = self.cos.shape[0]
+            if n > have:
+                c = np.empty((n, self.half), dtype=np.float32)
+                s = np.empty((n, self.half), dtype=np.float32)
+                c[:have], s[:have] = self.cos, self.sin
+                for a in range(have, n, chunk):
+                    e = min(a + chunk, n)
+                    ang = np.arange(a, e, dtype=np.int64)[:, None].astype(np.float64) * self.inv_freq[None, :]
+                    c[a:e] = np.cos(ang).astype(np.float32)
+                    s[a:e] = np.sin(ang).astype(np.float32)
+                self.cos, self.sin = c, s
+            return self.cos, self.sin
+
+
+_ROPE_TABLES: Dict[int, _RopeTable] = {}
+_ROPE_TABLES_LOCK = threading.Lock()
+
+
+def _rope_table(half: int) -> _RopeTable:
+    with _ROPE_TABLES_LOCK:
+        if half not in _ROPE_TABLES:
+            _ROPE_TABLES[half] = _RopeTable(half)
+        return _ROPE_TABLES[half]
+
+
+def release_tables() -> None:
+    """Drop the cached rotary tables (0.5 GB at one million positions)."""
+    with _ROPE_TABLES_LOCK:
+        _ROPE_TABLES.clear()
+
+
+def _rope_inplace(x: np.ndarray, n_pos: int, chunk: int = 1 << 15) -> None:
+    """Rotate row r of x ([n, d] float32) by position r, r = 0 .. n-1, in place."""
     n, d = x.shape
+    assert n == n_pos
     half = d // 2
-    inv_freq = ROPE_BASE ** (-np.arange(half, dtype=np.float64) / half)
+    cos, sin = _rope_table(half).upto(n)
     for s in range(0, n, chunk):
         e = min(s + chunk, n)
-        ang = positions[s:e, None].astype(np.float64) * inv_freq[None, :]
-        c = np.cos(ang).astype(np.float32)
-        sn = np.sin(ang).astype(np.float32)
+        c, sn = cos[s:e], sin[s:e]
         a = x[s:e, :half].copy()
         b = x[s:e, half:]
         x[s:e, :half] = a * c - b * sn
         x[s:e, half:] = b * c + a * sn
 
 
-def _rope_of_vector(w: np.ndarray, positions: np.ndarray) -> np.ndarray:
-    """rope(w, pos) for one vector w [d] at many positions -> [n, d] float32."""
-    out = np.broadcast_to(w.astype(np.float32), (positions.shape[0], w.shape[0])).copy()
-    _rope_inplace(out, positions)
+def _rope_of_vector(w: np.ndarray, n_pos: int) -> np.ndarray:
+    """rope(w, pos) for one vector w [d] at positions 0 .. n_pos-1 -> [n_pos, d] float32."""
+    out = np.broadcast_to(w.astype(np.float32), (n_pos, w.shape[0])).copy()
+    _rope_inplace(out, n_pos)
     return out
 
 
@@ -160,8 +217,7 @@ def _structure(wl: Workload, kv_head: int, seed: int):
     rng = np.random.default_rng([seed, wl.config_id, kv_head, 0])
     k = rng.standard_normal((S, d), dtype=np.float32)
     v = rng.standard_normal((S, d), dtype=np.float32)
-    pos = np.arange(S, dtype=np.int64)
-    _rope_inplace(k, pos)
+    _rope_inplace(k, S)
 
     slash_offsets = np.zeros(0, dtype=np.int64)
     slash_vecs = np.zeros((0, d), dtype=np.float32)
@@ -172,7 +228,7 @@ def _structure(wl: Workload, kv_head: int, seed: int):
         slash_offsets = np.sort(rng.choice(np.arange(lo, hi), size=wl.n_slash, replace=False))
         slash_vecs = (wl.slash_scale * rng.standard_normal((wl.n_slash, d))).astype(np.float32)
         for w_o in slash_vecs:
-            k += _rope_of_vector(w_o, pos)
+            k += _rope_of_vector(w_o, S)
 
     u = np.zeros(d, dtype=np.float32)
     sink_pos = np.zeros(0, dtype=np.int64)
@@ -191,32 +247,52 @@ def make_group(
     kv_head: int,
     seed: int = DEFAULT_SEED,
     q_heads: Optional[Sequence[int]] = None,
+    q_out: Optional[np.ndarray] = None,
+    workers: int = 1,
+    progress: Optional[Callable[[str], None]] = None,
 ):
     """Inputs of one KV head and (some of) the query heads that share it.
 
     Returns a dict with bf16 bit patterns (uint16): ``q`` [len(q_heads), S, d],
     ``k`` [S, d], ``v`` [S, d]; plus ``sink_pos``, ``slash_offsets`` and the
-    list ``q_heads`` (indices *within the group*, default all).
+    list ``q_heads`` (indices *within the group*, default all).  ``q_out``, if
+    given, receives the query heads (same shape).  ``workers`` threads draw the
+    query heads side by side (every head has a random stream of its own, so the
+    result does not depend on it); ``progress`` is called with a short message
+    after each finished part.
     """
     S, d = wl.seq_len, wl.head_dim
+    say = progress or (lambda msg: None)
     k, v, u, sink_pos, slash_offsets, slash_vecs = _structure(wl, kv_head, seed)
+    say(f"{wl.name}: kv head {kv_head}: K, V and planted structure drawn")
     heads = list(range(wl.group)) if q_heads is None else list(q_heads)
-    pos = np.arange(S, dtype=np.int64)
 
     # the planted query-side addend is shared by every head of the group
     q_add = np.zeros((S, d), dtype=np.float32)
     for o, w_o in zip(slash_offsets, slash_vecs):
-        q_add[o:] += _rope_of_vector(w_o, pos[: S - o])
+        q_add[o:] += _rope_of_vector(w_o, S - int(o))
     if wl.n_sinks > 0:
         q_add += wl.q_bias * u[None, :]
 
-    q_bits = np.empty((len(heads), S, d), dtype=np.uint16)
-    for n, g in enumerate(heads):
-        rng = np.random.default_rng([seed, wl.config_id, kv_head, 1 + g])
+    q_bits = np.empty((len(heads), S, d), dtype=np.uint16) if q_out is None else q_out
+    assert q_bits.shape == (len(heads), S, d) and q_bits.dtype == np.uint16
+
+    def one_head(n: int) -> int:
+        rng = np.random.default_rng([seed, wl.config_id, kv_head, 1 + heads[n]])
         q = rng.standard_normal((S, d), dtype=np.float32)
-        _rope_inplace(q, pos)
+        _rope_inplace(q, S)
         q += q_add
         q_bits[n] = f32_to_bf16_bits(q)
+        return n
+
+    if workers > 1 and len(heads) > 1:
+        with ThreadPoolExecutor(max_workers=min(workers, len(heads))) as pool:
+            for n in pool.map(one_head, range(len(heads))):
+                say(f"{wl.name}: kv head {kv_head}: query head {heads[n]} of the group done")
+    else:
+        for n in range(len(heads)):
+            one_head(n)
+            say(f"{wl.name}: kv head {kv_head}: query head {heads[n]} of the group done")
     return {
         "q": q_bits,
         "k": f32_to_bf16_bits(k),
@@ -227,19 +303,31 @@ def make_group(
     }
 
 
-def make_inputs(wl: Workload, seed: int = DEFAULT_SEED, kv_heads: Optional[Iterable[int]] = None):
+def default_workers(wl: Workload) -> int:
+    """Threads for make_inputs: a few at large sizes (each holds about 12 bytes per
+    query element while it works), one for small workloads."""
+    if wl.seq_len < 16384:
+        return 1
+    return max(1, min(8, (os.cpu_count() or 2) // 2))
+
+
+def make_inputs(wl: Workload, seed: int = DEFAULT_SEED, kv_heads: Optional[Iterable[int]] = None,
+                workers: Optional[int] = None, progress: Optional[Callable[[str], None]] = None):
     """All heads of a workload: ``q`` [Hq, S, d], ``k``/``v`` [Hkv, S, d] as
-    bf16 bit patterns (uint16), query head h using KV head h // group."""
+    bf16 bit patterns (uint16), query head h using KV head h // group.  The result
+    is the same for any ``workers``; ``progress`` as in make_group."""
     kvs = list(range(wl.n_kv_heads)) if kv_heads is None else list(kv_heads)
     S, d, G = wl.seq_len, wl.head_dim, wl.group
+    nw = default_workers(wl) if workers is None else workers
     q = np.empty((len(kvs) * G, S, d), dtype=np.uint16)
     k = np.empty((len(kvs), S, d), dtype=np.uint16)
     v = np.empty((len(kvs), S, d), dtype=np.uint16)
     meta = []
     for n, kv in enumerate(kvs):
-        g = make_group(wl, kv, seed)
-        q[n * G:(n + 1) * G] = g["q"]
+        g = make_group(wl, kv, seed, q_out=q[n * G:(n + 1) * G], workers=nw, progress=progress)
         k[n] = g["k"]
         v[n] = g["v"]
         meta.append({"sink_pos": g["sink_pos"], "slash_offsets": g["slash_offsets"]})
+    if S >= (1 << 19):
+        release_tables()
     return {"q": q, "k": k, "v": v, "meta": meta}

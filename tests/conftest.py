@@ -8,8 +8,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+HERE = os.path.dirname(os.path.abspath(__file__))
+if HERE not in sys.path:
+    sys.path.insert(0, HERE)
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    import gpu_progress
+    gpu_progress.set_config(config)
 
 
 def _gpu_available() -> bool:

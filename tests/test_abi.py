@@ -131,6 +131,8 @@ def test_select_and_sparse_validation(lib, B):
                                     idx, FAKE, FAKE, FAKE, None, 0, None)
 
     assert sel(-0.1, 0.5) == SA_INVALID
+    assert sel(1.5, 0.5) == SA_INVALID                                       # thresholds are fractions
+    assert sel(0.5, float("inf")) == SA_INVALID
     assert sel(0.5, float("nan")) == SA_INVALID
     assert sel(0.5, 0.5, idx=None) == SA_INVALID
 

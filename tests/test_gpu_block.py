@@ -19,8 +19,7 @@ pytestmark = pytest.mark.gpu
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3
 
 
-def _say(msg):
-    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+from gpu_progress import record as _record, say as _say  # noqa: E402
 
 
 def _dev(bits):
@@ -207,10 +206,11 @@ def test_block_pipeline_end_to_end(name, S, Hq, Hkv, gain, n_s):
         for got, want, scores, nm in ((gc, res["col_blocks"], res["col_block_scores"], "col"),
                                       (gs, res["slash_blocks"], res["slash_block_scores"], "slash")):
             diff = np.setxor1d(got, want)
-            _say(f"h{h} {nm}: gpu {len(got)} oracle {len(want)} differing {len(diff)}")
-            if len(diff):
-                cut = scores[want].min()
-                gap = np.abs(scores[diff] - cut).max() / cut
-                assert gap < 1e-3, (nm, h, gap)
+            gap = float(np.abs(scores[diff] - scores[want].min()).max() / scores[want].min()) if len(diff) else 0.0
+            _say(f"h{h} {nm}: gpu {len(got)} oracle {len(want)} differing {len(diff)}, gap {gap:.2e}")
+            _record(f"block pipeline {name} S={S}/h{h}/{nm}/strip_sets",
+                    {"gpu": int(len(got)), "oracle": int(len(want)), "differing": int(len(diff)),
+                     "largest_rel_gap_to_cut": gap})
+            assert gap <= 2.5e-4, (nm, h, gap)       # twice the 1e-4 score tolerance, plus a little
         want_out, _ = O.block_masked_attn(qf[h], kf[h // G], vf[h // G], gc, gs, w, blk)
         _check_out(out[0, h].float().cpu().numpy(), want_out, f"block pipeline out h{h}")

@@ -17,8 +17,7 @@ pytestmark = pytest.mark.gpu
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3
 
 
-def _say(msg):
-    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+from gpu_progress import record as _record, say as _say  # noqa: E402
 
 
 def _dev(bits):
@@ -160,11 +159,12 @@ def test_chunked_pipeline_end_to_end(name, S, Hq, Hkv, C, gain, blk):
             for got, want, scores, nm in ((gc[m], res["col_idx"][m], res["col"][m], "col"),
                                           (gs[m], res["slash_idx"][m], res["slash"][m], "slash")):
                 diff = np.setxor1d(got, want)
-                if len(diff):
-                    cut = scores[want].min()
-                    gap = np.abs(scores[diff] - cut).max() / cut
-                    _say(f"h{h} chunk {m} {nm}: {len(diff)} differing, gap {gap:.2e}")
-                    assert gap < 1e-3, (nm, h, m, gap)
+                gap = float(np.abs(scores[diff] - scores[want].min()).max() / scores[want].min()) if len(diff) else 0.0
+                _say(f"h{h} chunk {m} {nm}: {len(diff)} differing, gap {gap:.2e}")
+                _record(f"chunked pipeline S={S} blk={blk} C={C}/h{h}/chunk{m}/{nm}/strip_sets",
+                        {"gpu": int(len(got)), "oracle": int(len(want)), "differing": int(len(diff)),
+                         "largest_rel_gap_to_cut": gap})
+                assert gap <= 2.5e-4, (nm, h, m, gap)   # twice the 1e-4 score tolerance, plus a little
         want_out, _ = O.chunked_masked_attn(qf[h], kf[h // G], vf[h // G], gc, gs, w, C, blk=blk)
         _check_out(out[0, h].float().cpu().numpy(), want_out, f"chunked pipeline out h{h}")
 

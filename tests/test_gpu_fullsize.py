@@ -3,9 +3,18 @@ bench.py times (preallocated plan, three chained library calls).  The oracle
 cannot run these sizes end to end in seconds, so it is applied to sampled
 outputs it can compute one by one (single rows, single heads), plus properties
 that hold at any size (mass invariants, bit-exact selection on the GPU's own
-scores)."""
-import os
-import sys
+scores).
+
+Strip sets of the two pipelines (oracle scores -> oracle selection against GPU
+scores -> GPU selection) are compared on the heads whose oracle scores are
+computed: they may differ only in strips whose oracle score lies within
+STRIP_GAP_BOUND (relative) of the oracle's cut score.  The stated aim is 1e-6;
+it cannot be met by any fp32 stage 1, because sorted neighbours at the cut are
+closer than that to each other (5e-7 relative at 128K tokens) while the scores
+carry a relative error of up to 1e-4 (their tolerance): a strip can change
+sides when its own score and the cut score are both off by that much, hence
+2e-4, plus what the same error does to alpha * total (a shift of a few ranks,
+below 1e-5).  The measured gaps go to gpurun_out/parity_gaps.json."""
 
 import numpy as np
 import pytest
@@ -17,8 +26,7 @@ from sa_inputs import CONFIGS, bf16_bits_to_f32, make_inputs
 pytestmark = pytest.mark.gpu
 
 
-def _say(msg):
-    print(f"[gpu-case] {msg}", file=sys.stderr, flush=True)
+from gpu_progress import record as _record, say as _say  # noqa: E402
 
 
 def _dev(bits):
@@ -29,13 +37,26 @@ def _f64(bits):
     return bf16_bits_to_f32(bits).astype(np.float64)
 
 
+STRIP_GAP_BOUND = 2.5e-4
+
+
+def strip_set_gap(got, want, scores):
+    """(number of strips in one set only, largest |score - cut| / cut among them),
+    scores and cut taken from the oracle (cut = smallest selected oracle score)."""
+    diff = np.setxor1d(got, want)
+    if len(diff) == 0 or len(want) == 0:
+        return int(len(diff)), 0.0
+    cut = scores[want].min()
+    return int(len(diff)), float(np.abs(scores[diff] - cut).max() / cut)
+
+
 def _run_full(name, alpha, score_heads, attn_heads, n_rows, lse_rows):
     import paper_2406_15486_amd as sa
     wl = CONFIGS[name]
     S, Hq, Hkv, n_s, w = wl.seq_len, wl.n_q_heads, wl.n_kv_heads, wl.n_sample_rows, wl.window
     G = Hq // Hkv
     _say(f"{name}: generating inputs S={S}")
-    x = make_inputs(wl)
+    x = make_inputs(wl, progress=_say if S >= (1 << 19) else None)
     q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
     plan = sa.SampleAttentionPlan(sa.Shape(1, Hq, Hkv, S), n_s)
     _say(f"{name}: GPU path")
@@ -64,7 +85,17 @@ def _run_full(name, alpha, score_heads, attn_heads, n_rows, lse_rows):
         for got, want, nm in ((col[h], wc, "col"), (slash[h], ws, "slash")):
             worst = (np.abs(got - want) / (1e-4 * np.abs(want) + 1e-6)).max()
             _say(f"   {nm}: worst err/bound {worst:.3f}")
+            _record(f"{name}/h{h}/{nm}/score_err_over_bound", float(worst))
             assert worst <= 1.0, (nm, h, worst)
+        # the two pipelines end to end: oracle selection on the oracle's fp64 scores
+        # against the GPU's lists
+        for got, scores, nm in ((ci[h, :cc[h]], wc, "col"), (si[h, :sc[h]], ws, "slash")):
+            want = O.select(scores, a32)
+            n_diff, gap = strip_set_gap(got, want, scores)
+            _say(f"   {nm}: gpu keeps {len(got)}, oracle {len(want)}, {n_diff} differ, largest gap to the cut {gap:.3e}")
+            _record(f"{name}/h{h}/{nm}/strip_sets", {"gpu": int(len(got)), "oracle": int(len(want)),
+                                                    "differing": n_diff, "largest_rel_gap_to_cut": gap})
+            assert gap <= STRIP_GAP_BOUND, (nm, h, gap)
 
     # log-sum-exp of a few sampled rows (cheap at any size)
     if lse_rows:
@@ -96,14 +127,20 @@ def _run_full(name, alpha, score_heads, attn_heads, n_rows, lse_rows):
         assert err.max() <= 2e-2 and err.mean() <= 2e-3
 
 
+def test_glm8k_full_config():
+    """Second configuration at its stated size: S = 8192, 32 / 2 heads, 16 sinks per KV
+    head, 448 sampled rows.  The oracle does whole heads in seconds here."""
+    _run_full("glm8k", 0.95, score_heads=[0, 9, 18, 31], attn_heads=[0, 15, 16, 31], n_rows=256, lse_rows=32)
+
+
 def test_glm32k_full_config():
     _run_full("glm32k", 0.95, score_heads=[0, 21], attn_heads=[0, 13, 31], n_rows=96, lse_rows=32)
 
 
 def test_glm128k_benchmark_config():
-    # the benchmark's workload; whole-head oracle scores would take minutes, so
-    # stage 1 is checked through row log-sum-exps, invariants and reproducibility
-    _run_full("glm128k", 0.95, score_heads=[], attn_heads=[5, 30], n_rows=40, lse_rows=24)
+    # the benchmark's workload: stage-1 scores of two whole heads (one per KV head)
+    # element by element at n_s = 6592, a few seconds of oracle each
+    _run_full("glm128k", 0.95, score_heads=[0, 17], attn_heads=[5, 30], n_rows=40, lse_rows=24)
 
 
 def test_glm128k_block_granularity():
@@ -198,9 +235,9 @@ def test_glm128k_two_chunks_block_granularity():
     assert (tiles.cpu().numpy() > 0).all()
 
 
-@pytest.mark.skipif(os.environ.get("SA_TEST_1M") != "1",
-                    reason="1M tokens: two minutes of host-side input generation; set SA_TEST_1M=1 (and run with -s)")
 def test_glm1m_long_config():
     """The 1M-token configuration (2 % sampling): selection bit-exact on every head,
-    mass invariants, strip-masked and dense outputs on sampled rows of two heads."""
-    _run_full("glm1m", 0.95, score_heads=[], attn_heads=[2, 27], n_rows=48, lse_rows=8)
+    mass invariants, strip-masked and dense outputs on 256 seeded rows (128 in each
+    of two heads, one per KV head).  Input generation takes a minute or two on the
+    host; it reports every finished head."""
+    _run_full("glm1m", 0.95, score_heads=[], attn_heads=[2, 27], n_rows=128, lse_rows=8)
