@@ -52,7 +52,9 @@ typedef enum {
   SA_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, value out of range */
   SA_ERR_UNSUPPORTED = 2, /* a valid request this build does not implement       */
   SA_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or too small          */
-  SA_ERR_DEVICE = 4       /* the HIP runtime reported an error on launch         */
+  SA_ERR_DEVICE = 4,      /* the HIP runtime reported an error on launch         */
+  SA_ERR_TOO_LARGE = 5    /* sa_dense_attn_static: needs more than its static
+                             scratch holds                                       */
 } sa_status;
 
 /* Problem shape.  head_dim must be 128 and causal must be 1 (the method is
@@ -256,6 +258,26 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
 sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
                         void* out, int out_dtype, float* out_lse,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * sa_dense_attn for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, results and kernels as sa_dense_attn, but
+ * the transposed copy of V lives in a device array that is part of the library
+ * (SA_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of a
+ * caller workspace, and the call allocates nothing.
+ * Limit: batch * n_kv_heads * head_dim * roundup(seq_len, 256) * 2 bytes must
+ * fit the array, i.e. batch * n_kv_heads * roundup(seq_len, 256) <= 65536 -
+ * otherwise SA_ERR_TOO_LARGE, before anything is launched.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams or threads) race.  The array keeps the last
+ * call's contents; every call rewrites the part it reads.  The first call on
+ * a device looks up the array's address (hipGetSymbolAddress, with the
+ * caller's current device): make it outside any graph capture.
+ */
+#define SA_STATIC_SCRATCH_BYTES (16u << 20)
+sa_status sa_dense_attn_static(const sa_shape* shape, const void* q, const void* k, const void* v,
+                               void* out, int out_dtype, float* out_lse, void* stream);
 
 /*
  * Measurement aid (no part of the method).  While enabled, the library

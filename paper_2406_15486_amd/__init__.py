@@ -23,6 +23,8 @@ from .binding import (  # noqa: F401
     sa_select_chunked,
     sa_sparse_attn_chunked,
     sa_dense_attn,
+    sa_dense_attn_static,
+    SA_STATIC_SCRATCH_BYTES,
     sa_profile_enable,
     sa_profile_read,
     sa_rows_from_ratio,

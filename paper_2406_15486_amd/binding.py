@@ -111,6 +111,8 @@ def load_library() -> ctypes.CDLL:
     lib.sa_dense_attn.restype = ctypes.c_int
     lib.sa_dense_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p,
                                   vp, ctypes.c_size_t, vp]
+    lib.sa_dense_attn_static.restype = ctypes.c_int
+    lib.sa_dense_attn_static.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p, vp]
     lib.sa_profile_enable.restype = ctypes.c_int
     lib.sa_profile_enable.argtypes = [ctypes.c_int]
     lib.sa_profile_read.restype = ctypes.c_int
@@ -375,6 +377,31 @@ def sa_dense_attn(q, k, v, scale: float = 0.0, out_dtype: int = SA_OUT_BF16, wor
     if st != 0:
         raise SaError(st, "sa_dense_attn")
     return out, lse
+
+
+SA_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def sa_dense_attn_static(q, k, v, out, scale: float = 0.0, lse=None):
+    """sa_dense_attn for callers that cannot allocate: the caller passes the output
+    (bf16 or fp32, q's shape) and, optionally, the log-sum-exp buffer; the library
+    keeps its scratch in a static device array.  Nothing is allocated here either."""
+    lib = load_library()
+    sh = _shape_of(q, k, scale)
+    _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
+    _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
+    _check(v, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "v")
+    if out.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("out must be bf16 or fp32")
+    _check(out, out.dtype, tuple(q.shape), "out")
+    if lse is not None:
+        _check(lse, torch.float32, (sh.n_bh, sh.seq_len), "lse")
+    cs = sh.c()
+    st = lib.sa_dense_attn_static(ctypes.byref(cs), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                  SA_OUT_F32 if out.dtype == torch.float32 else SA_OUT_BF16, _ptr(lse), _stream())
+    if st != 0:
+        raise SaError(st, "sa_dense_attn_static")
+    return out
 
 
 SA_KERNELS = {"row_lse": 0, "score_accum": 1, "score_final": 2, "select": 3, "mask_prep": 4,

@@ -4,8 +4,14 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/sa.h"
 #include "sa_kernels.h"
+
+// Static device scratch of the entry point that allocates nothing (sa_dense_attn_static):
+// one copy per GPU that loads the library, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[SA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -153,6 +159,27 @@ struct Scope {   // records start now and stop at destruction
     g_prof.count[k]++;
   }
 };
+
+// ---- address of the static scratch array on the current device ------------------
+// In host code the array's name is only a handle for the runtime, not a device
+// address: the address is looked up once per device (with that device current) and
+// kept; kernels, fills and copies get that pointer.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+sa_status static_scratch(void** out) {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return SA_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SA_ERR_DEVICE;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return SA_OK;
+}
 
 sa::FlashParams base_flash(const Dims& d, const void* q, const void* k) {
   sa::FlashParams P;
@@ -558,6 +585,32 @@ sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, con
   return dev(sa::launch_flash(0, out_dtype == SA_OUT_F32, P, st));
 }
 
+sa_status sa_dense_attn_static(const sa_shape* shape, const void* q, const void* k, const void* v,
+                               void* out, int out_dtype, float* out_lse, void* stream) {
+  Dims d;
+  sa_status s = check_shape(shape, &d);
+  if (s != SA_OK) return s;
+  if (q == nullptr || k == nullptr || v == nullptr || out == nullptr) return SA_ERR_INVALID_ARG;
+  if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
+  if (dense_ws(d) > (size_t)SA_STATIC_SCRATCH_BYTES) return SA_ERR_TOO_LARGE;   // V^T must fit the static array
+  void* ws = nullptr;
+  s = static_scratch(&ws);
+  if (s != SA_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint16_t* vt = static_cast<uint16_t*>(ws);
+  // V^T is rewritten, zero padding included, up to the last key tile the kernel reads:
+  // nothing of an earlier call's contents is used
+  {
+    Scope sc(SA_K_TRANSPOSE_V, st);
+    s = dev(transpose_v(d, v, vt, st));
+  }
+  if (s != SA_OK) return s;
+  sa::FlashParams P = base_flash(d, q, k);
+  P.vt = vt; P.out = out; P.lse = out_lse;
+  Scope sc(SA_K_DENSE_FLASH, st);
+  return dev(sa::launch_flash(0, out_dtype == SA_OUT_F32, P, st));
+}
+
 sa_status sa_profile_enable(int enable) {
   if (enable && !g_prof.created) {
     for (int k = 0; k < SA_K_COUNT; ++k)
@@ -594,10 +647,11 @@ const char* sa_status_string(int status) {
     case SA_ERR_UNSUPPORTED: return "unsupported configuration";
     case SA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SA_ERR_DEVICE: return "HIP runtime error";
+    case SA_ERR_TOO_LARGE: return "problem exceeds the static scratch of the entry point that allocates nothing";
     default: return "unknown status";
   }
 }
 
-int sa_version(void) { return 120; }
+int sa_version(void) { return 130; }
 
 }  // extern "C"

@@ -207,6 +207,17 @@ def test_chunked_entry_points_validation(lib, B):
     assert attn(B._CSampling(0, 2, 128)) == SA_WORKSPACE
 
 
+def test_static_scratch_entry_point_limit(lib, B):
+    """sa_dense_attn_static keeps V^T in a 16 MiB static device array: a shape that needs
+    more is refused before anything is launched."""
+    fits = B._CShape(1, 4, 2, 32768, 128, 1, 0.0)          # 2 * 32768 * 128 * 2 bytes = 16 MiB exactly
+    too_big = B._CShape(1, 4, 2, 32769, 128, 1, 0.0)
+    assert lib.sa_dense_attn_static(ctypes.byref(too_big), FAKE, FAKE, FAKE, FAKE, 0, None, None) == 5
+    assert lib.sa_dense_attn_static(ctypes.byref(fits), FAKE, FAKE, FAKE, None, 0, None, None) == SA_INVALID
+    assert lib.sa_dense_attn_static(ctypes.byref(fits), FAKE, FAKE, FAKE, FAKE, 7, None, None) == SA_INVALID
+    assert b"static scratch" in lib.sa_status_string(5)
+
+
 def test_profile_read_before_enable(lib):
     buf = (ctypes.c_float * 4)()
     assert lib.sa_profile_read(99, buf, 4) == -1
