@@ -7,7 +7,9 @@ with the inputs already resident in HBM.  Prints ONE JSON line:
 
   metric  sparse prefill attention ms/layer (the headline metric) on the
           workload named in config.workload (default: the S=128K ChatGLM3-6B-
-          shaped config, alpha = 0.95, literal generator constants)
+          shaped config, alpha = 0.95, literal generator constants); value is
+          the median of the per-step durations between HIP events on the launch
+          stream, ms_per_step the wall-clock mean over the same steps
   roofline      the strip-masked flash kernel against the bf16 MFMA peak:
                 4*d*(computed 32x64 tiles) flop / mean kernel duration taken
                 from HIP events the library records around the launch, on the
@@ -16,10 +18,11 @@ with the inputs already resident in HBM.  Prints ONE JSON line:
                 same workload, extrapolated linearly to one layer
 
 Everything else on the line (per-stage times, the in-library dense kernel,
-speedup, kept fractions, alpha sweep with the recall of each mask, the same
-workload at block granularity and with two chunks) is context.  --alpha-grid
-adds separate column / slash thresholds; --sampling-study replaces the run by
-a comparison of sampled against full scores.
+speedup, kept fractions, useful rate, alpha sweep with the recall of each mask,
+the same workload at block granularity and with two chunks, separate column /
+slash thresholds on heads of one pattern each, the peaks this GPU reaches on a
+bare MFMA loop and a plain copy) is context.  --sampling-study replaces the run
+by a comparison of sampled against full scores.
 """
 from __future__ import annotations
 
@@ -50,16 +53,24 @@ def to_device(bits: np.ndarray):
     return t[None].contiguous().cuda()
 
 
+def kept_pairs_per_row(S: int, cols: np.ndarray, offs: np.ndarray, window: int) -> np.ndarray:
+    """Number of kept keys in every row of the strip mask of one head: selected columns at
+    or before the row, plus kept offsets (selected or inside the window) that fit, minus
+    the pairs that are both - a correlation of the two indicator vectors, taken with an
+    FFT (counting only; exact after rounding)."""
+    c = np.zeros(S)
+    c[np.asarray(cols, dtype=np.int64)] = 1.0
+    o = np.zeros(S)
+    o[np.asarray(offs, dtype=np.int64)] = 1.0
+    o[:window] = 1.0
+    n = 1 << int(np.ceil(np.log2(2 * S)))
+    both = np.fft.irfft(np.fft.rfft(c, n) * np.fft.rfft(o, n), n)[:S]      # both[i] = sum_j c[j] o[i - j]
+    return np.cumsum(c) + np.cumsum(o) - np.rint(both)
+
+
 def mask_density(S: int, cols: np.ndarray, offs: np.ndarray, window: int) -> float:
-    """Kept fraction of the causal triangle for one head (counting only)."""
-    off_keep = np.zeros(S, dtype=bool)
-    off_keep[offs] = True
-    off_keep[:window] = True
-    oo = np.nonzero(off_keep)[0]
-    n_col = int(np.sum(S - cols.astype(np.int64)))
-    n_off = int(np.sum(S - oo))
-    both = int(np.sum(np.searchsorted(oo, S - 1 - cols.astype(np.int64), side="right")))
-    return (n_col + n_off - both) / (S * (S + 1) / 2.0)
+    """Kept fraction of the causal triangle for one head."""
+    return float(kept_pairs_per_row(S, cols, offs, window).sum() / (S * (S + 1) / 2.0))
 
 
 def touched_block_fraction(S: int, cols: np.ndarray, offs: np.ndarray, window: int, blk: int = 128) -> float:
@@ -207,8 +218,8 @@ def sampling_study(sa, torch, wl, q, k, v, shape) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="glm128k")
     ap.add_argument("--seq-len", type=int, default=0, help="override the workload's sequence length")
     ap.add_argument("--alpha", type=float, default=0.95)
@@ -218,8 +229,9 @@ def main() -> int:
     ap.add_argument("--no-sweep", action="store_true", help="skip the alpha sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block", action="store_true", help="skip the block-granularity runs")
-    ap.add_argument("--alpha-grid", action="store_true",
-                    help="also run a grid of separate column / slash thresholds (alpha_c x alpha_s)")
+    ap.add_argument("--no-alpha-grid", action="store_true",
+                    help="skip the grid of separate column / slash thresholds on the three head patterns")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the MFMA / copy peak probes")
     ap.add_argument("--sampling-study", action="store_true",
                     help="compare masks chosen from sampled scores with masks chosen from the scores of ALL rows "
                          "at equal strip budgets (recall of the dense softmax), then exit")
@@ -273,16 +285,22 @@ def main() -> int:
         plan.run(q, k, v, args.alpha, args.alpha, w)
     torch.cuda.synchronize()
     sa.sa_profile_enable(True)
+    # an event pair per step on the launch stream (the library enqueues on torch's current stream)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for e0, e1 in ev:
+        e0.record()
         plan.run(q, k, v, args.alpha, args.alpha, w)
+        e1.record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    step_ms = [e0.elapsed_time(e1) for e0, e1 in ev]
+    ms_median = float(np.median(step_ms))
     stage = {name: sa.sa_profile_read(name) for name in
-             ("row_lse", "score_accum", "score_final", "select", "mask_prep", "sparse_flash")}
+             ("row_lse", "score_accum", "score_final", "select", "transpose_v", "mask_prep", "sparse_flash")}
     stage_ms = {n: (float(np.mean(vv)) if vv else None) for n, vv in stage.items()}
-    log(f"ms/step {ms_per_step:.3f}; stages {json.dumps(stage_ms)}")
+    log(f"ms/step: median of events {ms_median:.3f}, wall-clock mean {ms_per_step:.3f}; stages {json.dumps(stage_ms)}")
 
     tiles = plan.tiles.cpu().numpy().astype(np.int64)
     flash_ms = stage_ms["sparse_flash"]
@@ -296,6 +314,17 @@ def main() -> int:
     si = plan.slash_idx[0, :int(sc[0])].cpu().numpy()
     density0 = mask_density(S, ci, si, w)
     blocks0 = touched_block_fraction(S, ci, si, w)
+    # useful rate: 4 d flop per KEPT (query, key) pair of every head's mask over the same kernel time
+    ci_all, si_all = plan.col_idx.cpu().numpy(), plan.slash_idx.cpu().numpy()
+    kept_pairs = float(sum(kept_pairs_per_row(S, ci_all[h, :int(cc[h])], si_all[h, :int(sc[h])], w).sum()
+                           for h in range(Hq)))
+    useful_tflops = 4.0 * 128 * kept_pairs / (flash_ms * 1e-3) / 1e12
+    del ci_all, si_all
+    ws_bytes = {"sample_scores": sa.sa_workspace_bytes(sa.binding.SA_OP_SAMPLE_SCORES, shape, n_s),
+                "sparse_attn": sa.sa_workspace_bytes(sa.binding.SA_OP_SPARSE_ATTN, shape),
+                "sparse_attn_4_heads_per_pass": sa.sa_partitioned_workspace_bytes(shape, 4, 1),
+                "dense_attn": sa.sa_workspace_bytes(sa.binding.SA_OP_DENSE_ATTN, shape)}
+    log(f"workspace bytes: {json.dumps(ws_bytes)}")
     # stages 1-2 against HBM: algorithmic bytes (K once per KV head and pass, the sampled Q rows,
     # the row statistics, the two score vectors; five passes over the scores for the selection)
     kv_b, qr_b, lse_b, sc_b = Hkv * S * 128 * 2, Hq * n_s * 128 * 2, Hq * n_s * 4, 2 * Hq * S * 4
@@ -331,7 +360,7 @@ def main() -> int:
     # = exp(lse_masked_i - lse_dense_i); its minimum over rows is the CRA of the mask
     # (Sec. 3.3).  Both log-sum-exps are optional outputs of the attention kernels.
     dense_lse = None
-    if dense_ms is not None and (not args.no_sweep or not args.no_block or args.alpha_grid):
+    if dense_ms is not None and (not args.no_sweep or not args.no_block):
         plan.lse = torch.empty(Hq, S, dtype=torch.float32, device="cuda")
         plan.dense(q, k, v)
         torch.cuda.synchronize()
@@ -356,7 +385,7 @@ def main() -> int:
             plan.attend(q, k, v, w)
             torch.cuda.synchronize()
             t_sel = float(np.mean(sa.sa_profile_read("select")))
-            t_prep = float(np.mean(sa.sa_profile_read("mask_prep")))
+            t_prep = float(np.mean(sa.sa_profile_read("mask_prep"))) + float(np.mean(sa.sa_profile_read("transpose_v")))
             t_fl = float(np.mean(sa.sa_profile_read("sparse_flash")))
             tl = plan.tiles.cpu().numpy().astype(np.int64)
             stage1 = sum(stage_ms[n] for n in ("row_lse", "score_accum", "score_final"))
@@ -375,28 +404,6 @@ def main() -> int:
             })
             log(f"alpha {a}: {json.dumps(sweep[-1])}")
 
-    # ---- separate thresholds for columns and slashes (Sec. 4.1: alpha decomposed) -----
-    grid = []
-    if args.alpha_grid:
-        plan.sample(q, k)
-        for ac in (0.8, 0.9, 0.95):
-            for as_ in (0.8, 0.9, 0.95):
-                plan.select(ac, as_)
-                plan.attend(q, k, v, w)          # warm
-                torch.cuda.synchronize()
-                sa.sa_profile_enable(True)
-                plan.select(ac, as_)
-                plan.attend(q, k, v, w)
-                torch.cuda.synchronize()
-                t_fl = float(np.mean(sa.sa_profile_read("sparse_flash")))
-                tl = plan.tiles.cpu().numpy().astype(np.int64)
-                grid.append({
-                    "alpha_c": ac, "alpha_s": as_, "sparse_flash_ms": t_fl,
-                    "computed_tile_fraction": float(tl.sum()) / dense_tiles,
-                    "mean_k_c": float(plan.col_cnt.float().mean()), "mean_k_s": float(plan.slash_cnt.float().mean()),
-                    **(recall_stats(plan.lse) if plan.lse is not None else {}),
-                })
-                log(f"grid: {json.dumps(grid[-1])}")
     # ---- the same workload at block granularity (Algorithm 1 with blk = 128): with the
     #      workload's sampled rows, and with the paper's 128 sampled rows -----------------
     block_runs = []
@@ -416,7 +423,7 @@ def main() -> int:
                 torch.cuda.synchronize()
                 # a kernel runs once per chunk: the step's time is the sum of its launches
                 t = {n: float(np.sum(sa.sa_profile_read(n))) for n in
-                     ("row_lse", "score_accum", "score_final", "select", "mask_prep", "sparse_flash")}
+                     ("row_lse", "score_accum", "score_final", "select", "transpose_v", "mask_prep", "sparse_flash")}
                 tl = bplan.tiles.cpu().numpy().astype(np.int64)
                 cca, sca = bplan.col_cnt.cpu().numpy(), bplan.slash_cnt.cpu().numpy()
                 total = sum(t.values())
@@ -435,7 +442,81 @@ def main() -> int:
                 })
                 log(f"block: {json.dumps(block_runs[-1])}")
             del bplan
+    # ---- separate thresholds for columns and slashes (Sec. 4.1: alpha decomposed into alpha_c and
+    #      alpha_s; Sec. 5.3 studies them) on heads of one pattern each: strong columns only,
+    #      diagonals only, both.  Kept fraction, recall and CRA of the mask per (alpha_c, alpha_s).
+    grid = []
+    if not args.no_alpha_grid:
+        from sa_inputs import HEAD_PATTERNS
+        grid_alphas = (0.0, 0.8, 0.9, 0.95)
+        for pname, pwl in HEAD_PATTERNS.items():
+            pwl = pwl.scaled(S)
+            if S // 2 - 2 * pwl.window < pwl.n_slash:
+                continue
+            t0 = time.perf_counter()
+            px = make_inputs(pwl)
+            pq, pk, pv = to_device(px["q"]), to_device(px["k"]), to_device(px["v"])
+            del px
+            log(f"head pattern {pname}: inputs in {time.perf_counter() - t0:.1f} s")
+            plan.lse = torch.empty(Hq, S, dtype=torch.float32, device="cuda") if plan.lse is None else plan.lse
+            plan.dense(pq, pk, pv)
+            torch.cuda.synchronize()
+            p_dense_lse = plan.lse.clone()
+            plan.sample(pq, pk)
+            for ac in grid_alphas:
+                for as_ in grid_alphas:
+                    plan.select(ac, as_)
+                    plan.attend(pq, pk, pv, w)          # warm
+                    torch.cuda.synchronize()
+                    sa.sa_profile_enable(True)
+                    plan.select(ac, as_)
+                    plan.attend(pq, pk, pv, w)
+                    torch.cuda.synchronize()
+                    t_fl = float(np.mean(sa.sa_profile_read("sparse_flash")))
+                    tl = plan.tiles.cpu().numpy().astype(np.int64)
+                    cca, sca = plan.col_cnt.cpu().numpy(), plan.slash_cnt.cpu().numpy()
+                    r = torch.exp(plan.lse - p_dense_lse)
+                    grid.append({
+                        "head_pattern": pname, "alpha_c": ac, "alpha_s": as_, "sparse_flash_ms": t_fl,
+                        "computed_tile_fraction": float(tl.sum()) / dense_tiles,
+                        "mask_density_head0": mask_density(S, plan.col_idx[0, :int(cca[0])].cpu().numpy(),
+                                                           plan.slash_idx[0, :int(sca[0])].cpu().numpy(), w),
+                        "mean_k_c": float(cca.mean()), "mean_k_s": float(sca.mean()),
+                        "recall_mean": float(r.mean()), "cra_min": float(r.min()),
+                    })
+                    log(f"grid: {json.dumps(grid[-1])}")
+            del pq, pk, pv, p_dense_lse
     sa.sa_profile_enable(False)
+
+    # ---- what this GPU reaches on a bare MFMA loop and on a plain copy ---------------------
+    peaks = None
+    if not args.no_peaks:
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        peaks = {}
+        for wps in (1, 2):
+            sa.sa_probe_mfma(2000, wps, sink)            # warm
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            flop = sa.sa_probe_mfma(20000, wps, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            peaks[f"mfma_bf16_tflops_{wps}_waves_per_simd"] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        sa.sa_probe_copy(src, dst)
+        best = 0.0
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            moved = sa.sa_probe_copy(src, dst)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, moved / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        peaks["copy_1gib_read_plus_write_gbs"] = best
+        del src, dst
+        log(f"measured peaks: {json.dumps(peaks)}")
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -453,7 +534,7 @@ def main() -> int:
 
     line = {
         "metric": "sparse prefill attention ms/layer",
-        "value": ms_per_step,
+        "value": ms_median,
         "unit": "ms/layer",
         "n_gpus": 1,
         "steps": args.steps,
@@ -475,9 +556,16 @@ def main() -> int:
             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
             "traffic": traffic,
             "flop_per_launch": flop, "kernel_ms": flash_ms,
+            "useful_tflops": useful_tflops,
         },
         "cpu_baseline": cpu,
+        "timing": {"value": "median of per-step HIP-event durations on the launch stream",
+                   "ms_per_step": "wall-clock mean over the same steps", "step_ms": step_ms},
         "stage_ms": stage_ms,
+        "useful_tflops": useful_tflops,
+        "kept_pair_fraction": kept_pairs / (Hq * S * (S + 1) / 2.0),
+        "workspace_bytes": ws_bytes,
+        "measured_peaks": peaks,
         "computed_tile_fraction": float(tiles.sum()) / dense_tiles,
         "mask_density_head0": density0,
         "touched_128x128_block_fraction_head0": blocks0,
@@ -486,7 +574,7 @@ def main() -> int:
         "mean_k_c": float(cc.mean()), "mean_k_s": float(sc.mean()),
         "dense_ms": dense_ms,
         "dense_kernel_tflops": dense_kernel_tflops if dense_ms else None,
-        "speedup_vs_dense": (dense_ms / ms_per_step) if dense_ms else None,
+        "speedup_vs_dense": (dense_ms / ms_median) if dense_ms else None,
         "alpha_sweep": sweep,
         "block_granularity_runs": block_runs,
         "alpha_c_alpha_s_grid": grid,

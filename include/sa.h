@@ -252,6 +252,38 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * sa_sparse_attn with bounded workspace, for long sequences (Sec. 5.4: above
+ * 256K tokens the paper splits the sequence into chunks and partitions the
+ * attention by head "to avoid memory issues").  The heads are processed
+ * heads_per_pass at a time - the workspace then holds the metadata and the
+ * gathered K / V of one pass only, about
+ *   batch * n_kv_heads * S_pad * 256  +  heads_per_pass * S_pad * 520  bytes
+ * (S_pad = seq_len rounded up to 256) instead of the second term times all
+ * batch * n_q_heads heads - and the query rows of a pass in n_query_segments
+ * consecutive launches of (nearly) equal numbers of 256-row query tiles.
+ * Values larger than the number of heads / query tiles are clamped; both must
+ * be >= 1.  The result (out, out_lse, tiles) is bit-identical to
+ * sa_sparse_attn's: every (head, query tile) is computed by one workgroup in
+ * the same order of operations whatever the partition.
+ * Workspace: sa_partitioned_workspace_bytes(shape, partition) (0 for invalid
+ * arguments; host only).
+ */
+typedef struct {
+  int32_t heads_per_pass;
+  int32_t n_query_segments;
+} sa_partition;
+
+size_t sa_partitioned_workspace_bytes(const sa_shape* shape, const sa_partition* partition);
+
+sa_status sa_sparse_attn_partitioned(const sa_shape* shape, const sa_partition* partition,
+                                     const void* q, const void* k, const void* v,
+                                     const int32_t* col_idx, const int32_t* col_cnt,
+                                     const int32_t* slash_idx, const int32_t* slash_cnt,
+                                     int32_t local_window,
+                                     void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Dense causal attention (Eq. 1-2 with keys j <= i), the in-library baseline
  * the sparse path is compared against.  Same layouts and outputs as above.
  */
@@ -296,15 +328,30 @@ typedef enum {
   SA_K_SCORE_FINAL = 2,    /* stage 1: fixed-order sum of the partials, block
                               reduction                                            */
   SA_K_SELECT = 3,         /* stage 2: the selection launch (both directions)      */
-  SA_K_MASK_PREP = 4,      /* merge: bitmaps, tile-diagonal list, V^T, K/V gathers */
+  SA_K_MASK_PREP = 4,      /* merge: bitmaps, tile-diagonal list, K/V gathers (once
+                              per pass over a group of heads)                      */
   SA_K_SPARSE_FLASH = 5,   /* strip-masked flash attention kernel                  */
   SA_K_DENSE_FLASH = 6,    /* dense flash attention kernel                         */
-  SA_K_TRANSPOSE_V = 7,    /* V -> V^T of the dense path                           */
+  SA_K_TRANSPOSE_V = 7,    /* V -> V^T (dense and strip-masked paths)              */
   SA_K_COUNT = 8
 } sa_kernel_id;
 #define SA_PROFILE_SLOTS 64
 sa_status sa_profile_enable(int enable);
 int sa_profile_read(int kernel, float* ms, int cap);
+
+/*
+ * Measurement aids (no part of the method): what this GPU reaches on the two
+ * resources the kernels are priced against.  Both only enqueue; time them with
+ * events on `stream`.
+ * sa_probe_mfma: waves_per_simd (1..8) waves on each of the 1024 SIMDs issue
+ *   iters * 16 back-to-back 32x32x16 bf16 MFMAs (32768 flop each) from
+ *   registers: 1024 * waves_per_simd * iters * 16 * 32768 flop in all.  sink: a
+ *   device float, never written in practice.
+ * sa_probe_copy: a plain copy of bytes (a multiple of 16) from src to dst
+ *   (device pointers, 16-byte aligned): bytes read plus bytes written.
+ */
+sa_status sa_probe_mfma(int32_t iters, int32_t waves_per_simd, float* sink, void* stream);
+sa_status sa_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 const char* sa_status_string(int status);
 int sa_version(void);

@@ -25,12 +25,16 @@ from .binding import (  # noqa: F401
     sa_dense_attn,
     sa_dense_attn_static,
     SA_STATIC_SCRATCH_BYTES,
+    sa_probe_copy,
+    sa_probe_mfma,
     sa_profile_enable,
     sa_profile_read,
     sa_rows_from_ratio,
     sa_sample_scores,
     sa_select_strips,
     sa_sparse_attn,
+    sa_sparse_attn_partitioned,
+    sa_partitioned_workspace_bytes,
     sa_workspace_bytes,
     sample_attention,
 )

@@ -36,6 +36,10 @@ class _CShape(ctypes.Structure):
                 ("softmax_scale", ctypes.c_float)]
 
 
+class _CPartition(ctypes.Structure):
+    _fields_ = [("heads_per_pass", ctypes.c_int32), ("n_query_segments", ctypes.c_int32)]
+
+
 class _CSampling(ctypes.Structure):
     _fields_ = [("n_sample_rows", ctypes.c_int32), ("n_chunks", ctypes.c_int32),
                 ("granularity", ctypes.c_int32)]
@@ -111,8 +115,18 @@ def load_library() -> ctypes.CDLL:
     lib.sa_dense_attn.restype = ctypes.c_int
     lib.sa_dense_attn.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p,
                                   vp, ctypes.c_size_t, vp]
+    lib.sa_partitioned_workspace_bytes.restype = ctypes.c_size_t
+    lib.sa_partitioned_workspace_bytes.argtypes = [ctypes.POINTER(_CShape), ctypes.POINTER(_CPartition)]
+    lib.sa_sparse_attn_partitioned.restype = ctypes.c_int
+    lib.sa_sparse_attn_partitioned.argtypes = [ctypes.POINTER(_CShape), ctypes.POINTER(_CPartition), vp, vp, vp,
+                                               i32p, i32p, i32p, i32p, ctypes.c_int32, vp, ctypes.c_int, f32p, vp,
+                                               vp, ctypes.c_size_t, vp]
     lib.sa_dense_attn_static.restype = ctypes.c_int
     lib.sa_dense_attn_static.argtypes = [ctypes.POINTER(_CShape), vp, vp, vp, vp, ctypes.c_int, f32p, vp]
+    lib.sa_probe_mfma.restype = ctypes.c_int
+    lib.sa_probe_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, f32p, vp]
+    lib.sa_probe_copy.restype = ctypes.c_int
+    lib.sa_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     lib.sa_profile_enable.restype = ctypes.c_int
     lib.sa_profile_enable.argtypes = [ctypes.c_int]
     lib.sa_profile_read.restype = ctypes.c_int
@@ -359,6 +373,44 @@ def sa_sparse_attn(q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window
     return out, lse, tiles
 
 
+def sa_partitioned_workspace_bytes(shape: Shape, heads_per_pass: int, n_query_segments: int = 1) -> int:
+    cs, part = shape.c(), _CPartition(heads_per_pass, n_query_segments)
+    return int(load_library().sa_partitioned_workspace_bytes(ctypes.byref(cs), ctypes.byref(part)))
+
+
+def sa_sparse_attn_partitioned(q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window: int,
+                               heads_per_pass: int, n_query_segments: int = 1, scale: float = 0.0,
+                               out_dtype: int = SA_OUT_BF16, workspace=None, want_lse: bool = False,
+                               want_tiles: bool = False, out=None):
+    """sa_sparse_attn with the heads taken ``heads_per_pass`` at a time and the queries
+    in ``n_query_segments`` launches: same result, workspace for one pass only.
+    Returns (out, lse or None, tiles or None)."""
+    lib = load_library()
+    sh = _shape_of(q, k, scale)
+    _check(q, torch.bfloat16, (sh.batch, sh.n_q_heads, sh.seq_len, sh.head_dim), "q")
+    _check(k, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "k")
+    _check(v, torch.bfloat16, (sh.batch, sh.n_kv_heads, sh.seq_len, sh.head_dim), "v")
+    for t, nm in ((col_idx, "col_idx"), (slash_idx, "slash_idx")):
+        _check(t, torch.int32, (sh.n_bh, sh.seq_len), nm)
+    for t, nm in ((col_cnt, "col_cnt"), (slash_cnt, "slash_cnt")):
+        _check(t, torch.int32, (sh.n_bh,), nm)
+    cs, part = sh.c(), _CPartition(heads_per_pass, n_query_segments)
+    need = int(lib.sa_partitioned_workspace_bytes(ctypes.byref(cs), ctypes.byref(part)))
+    ws = workspace if workspace is not None else _workspace(need, q.device)
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.float32 if out_dtype == SA_OUT_F32 else torch.bfloat16,
+                          device=q.device)
+    lse = torch.empty(sh.n_bh, sh.seq_len, dtype=torch.float32, device=q.device) if want_lse else None
+    tiles = torch.empty(sh.n_bh, dtype=torch.int64, device=q.device) if want_tiles else None
+    st = lib.sa_sparse_attn_partitioned(ctypes.byref(cs), ctypes.byref(part), _ptr(q), _ptr(k), _ptr(v),
+                                        _ptr(col_idx), _ptr(col_cnt), _ptr(slash_idx), _ptr(slash_cnt),
+                                        int(local_window), _ptr(out), out_dtype, _ptr(lse), _ptr(tiles), _ptr(ws),
+                                        ws.numel() if ws is not None else 0, _stream())
+    if st != 0:
+        raise SaError(st, "sa_sparse_attn_partitioned")
+    return out, lse, tiles
+
+
 def sa_dense_attn(q, k, v, scale: float = 0.0, out_dtype: int = SA_OUT_BF16, workspace=None,
                   want_lse: bool = False):
     """Dense causal attention.  Returns (out, lse or None)."""
@@ -402,6 +454,23 @@ def sa_dense_attn_static(q, k, v, out, scale: float = 0.0, lse=None):
     if st != 0:
         raise SaError(st, "sa_dense_attn_static")
     return out
+
+
+def sa_probe_mfma(iters: int, waves_per_simd: int, sink) -> float:
+    """Enqueue the back-to-back MFMA probe; returns the flop it performs."""
+    st = load_library().sa_probe_mfma(int(iters), int(waves_per_simd), _ptr(sink), _stream())
+    if st != 0:
+        raise SaError(st, "sa_probe_mfma")
+    return 1024.0 * waves_per_simd * iters * 16 * 32768
+
+
+def sa_probe_copy(src, dst) -> int:
+    """Enqueue a plain copy src -> dst (uint8 CUDA tensors of equal size); returns bytes read + written."""
+    n = src.numel() * src.element_size()
+    st = load_library().sa_probe_copy(_ptr(src), _ptr(dst), n, _stream())
+    if st != 0:
+        raise SaError(st, "sa_probe_copy")
+    return 2 * n
 
 
 SA_KERNELS = {"row_lse": 0, "score_accum": 1, "score_final": 2, "select": 3, "mask_prep": 4,

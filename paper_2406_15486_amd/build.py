@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsampleattn.so")
-SOURCES = ["sa_api.hip", "flash_attn.hip", "prep.hip", "scores.hip", "select.hip"]
+SOURCES = ["sa_api.hip", "flash_attn.hip", "prep.hip", "scores.hip", "select.hip", "probes.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-munsafe-fp-atomics",

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       bh = bkv * P.group + hg;
     }
   }
-  const int bkv = bh / P.group;
+  const int bkv = ((MODE == 2 ? P.head0 : 0) + bh) / P.group;
   const int S = P.S;
   const int i0 = P.q_row0 + a * BQ;                     // first query row of the workgroup
   const int i_last_wg = min(i0 + BQ, P.q_row0 + P.n_qrows) - 1;  // last valid row

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(GatherParams P) {
     }
   }
   if (c0 >= ((cnt + 63) & ~63)) return;   // nothing reads beyond the last partial tile
-  const uint16_t* src = P.src + (size_t)(g / P.group) * P.S * kHeadDim;
+  const uint16_t* src = P.src + (size_t)((P.head0 + g) / P.group) * P.S * kHeadDim;
 #pragma unroll
   for (int n = 0; n < 4; ++n) {
     int c = tid + 256 * n;

@@ -100,7 +100,8 @@ struct SparseWs {
   size_t vt, kc, vct, cidx, cbits, obits, dlist, dcnt, total;
   int cb_words, rb_words, dlist_stride, off_max;
 };
-SparseWs sparse_ws(const Dims& d) {
+// n_heads: the (batch * query) heads whose metadata and gathered K/V are resident at once
+SparseWs sparse_ws(const Dims& d, int n_heads) {
   SparseWs w;
   w.cb_words = d.S_pad / 32 + 2;
   w.rb_words = d.S_pad / 32 + 24;
@@ -108,29 +109,39 @@ SparseWs sparse_ws(const Dims& d) {
   w.off_max = d.S_pad - 1;
   size_t at = 0;
   w.vt = at;    at += align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2);
-  w.kc = at;    at += align_up((size_t)d.n_bh * d.S_pad * sa::kHeadDim * 2);
-  w.vct = at;   at += align_up((size_t)d.n_bh * sa::kHeadDim * d.S_pad * 2);
-  w.cidx = at;  at += align_up((size_t)d.n_bh * d.S_pad * 4);
-  w.cbits = at; at += align_up((size_t)d.n_bh * w.cb_words * 4);
-  w.obits = at; at += align_up((size_t)d.n_bh * w.rb_words * 4);
-  w.dlist = at; at += align_up((size_t)d.n_bh * w.dlist_stride * 4);
-  w.dcnt = at;  at += align_up((size_t)d.n_bh * 4);
+  w.kc = at;    at += align_up((size_t)n_heads * d.S_pad * sa::kHeadDim * 2);
+  w.vct = at;   at += align_up((size_t)n_heads * sa::kHeadDim * d.S_pad * 2);
+  w.cidx = at;  at += align_up((size_t)n_heads * d.S_pad * 4);
+  w.cbits = at; at += align_up((size_t)n_heads * w.cb_words * 4);
+  w.obits = at; at += align_up((size_t)n_heads * w.rb_words * 4);
+  w.dlist = at; at += align_up((size_t)n_heads * w.dlist_stride * 4);
+  w.dcnt = at;  at += align_up((size_t)n_heads * 4);
   w.total = at;
   return w;
 }
 
 struct BlockWs { SparseWs sp; size_t tok_idx, tok_cnt, dbits, total; int nb, db_words; };
-BlockWs block_ws(const Dims& d, int blk) {
+BlockWs block_ws(const Dims& d, int blk, int n_heads) {
   BlockWs w;
-  w.sp = sparse_ws(d);
+  w.sp = sparse_ws(d, n_heads);
   w.nb = (d.S + blk - 1) / blk;
   w.db_words = (w.nb + 1) / 32 + 1;
   size_t at = w.sp.total;
-  w.tok_idx = at; at += align_up((size_t)d.n_bh * d.S * 4);
-  w.tok_cnt = at; at += align_up((size_t)d.n_bh * 4);
-  w.dbits = at;   at += align_up((size_t)d.n_bh * w.db_words * 4);
+  w.tok_idx = at; at += align_up((size_t)n_heads * d.S * 4);
+  w.tok_cnt = at; at += align_up((size_t)n_heads * 4);
+  w.dbits = at;   at += align_up((size_t)n_heads * w.db_words * 4);
   w.total = at;
   return w;
+}
+
+// heads per pass and query segments of a partitioned call, validated
+sa_status check_partition(const sa_partition* p, const Dims& d, int* heads_per_pass, int* n_segments) {
+  if (p == nullptr) return SA_ERR_INVALID_ARG;
+  if (p->heads_per_pass < 1 || p->n_query_segments < 1) return SA_ERR_INVALID_ARG;
+  *heads_per_pass = p->heads_per_pass < d.n_bh ? p->heads_per_pass : d.n_bh;
+  const int n_qtiles = d.S_pad / sa::kFlashBQ;
+  *n_segments = p->n_query_segments < n_qtiles ? p->n_query_segments : n_qtiles;
+  return SA_OK;
 }
 
 size_t dense_ws(const Dims& d) { return align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2); }
@@ -217,11 +228,11 @@ size_t sa_workspace_bytes(int op, const sa_shape* shape, const sa_sampling* samp
       if (check_sampling(sampling, d) != SA_OK) return 0;
       return sample_ws(d, sampling->n_sample_rows, sampling->granularity).total;
     case SA_OP_SELECT_STRIPS: return 0;
-    case SA_OP_SPARSE_ATTN: return sparse_ws(d).total;
+    case SA_OP_SPARSE_ATTN: return sparse_ws(d, d.n_bh).total;
     case SA_OP_DENSE_ATTN: return dense_ws(d);
     case SA_OP_BLOCK_SPARSE_ATTN:
       if (sampling == nullptr || check_granularity(sampling->granularity) != SA_OK) return 0;
-      return block_ws(d, sampling->granularity).total;
+      return block_ws(d, sampling->granularity, d.n_bh).total;
     default: return 0;
   }
 }
@@ -397,93 +408,108 @@ sa_status sa_select_chunked(const sa_shape* shape, const sa_sampling* sampling,
 }  // extern "C"
 
 namespace {
-// One segment of the queries (query tiles [qtile0, qtile0 + n_qtiles)) under the mask
-// of one set of lists: metadata (merge_index), gathers, then the strip-masked kernel.
+// merge_index for the heads [h0, h0 + nh) under one set of lists: bitmaps, tile-diagonal
+// list and the gathered K / V^T of the kept columns, all in workspace slots 0 .. nh-1.
 // granularity 1: strip lists (per key / per offset); otherwise lists of blocks.
-sa_status attend_segment(const Dims& d, const BlockWs& bw, int granularity, bool first_segment,
-                         int qtile0, int n_qtiles, const void* q, const void* k, const void* v,
-                         const int32_t* col_idx, const int32_t* col_cnt,
-                         const int32_t* slash_idx, const int32_t* slash_cnt, int32_t local_window,
-                         void* out, int out_dtype, float* out_lse, uint64_t* tiles, char* ws, hipStream_t st) {
+// On return *cnt_used points at the column counts the kernel must read (slot-indexed).
+sa_status prepare_heads(const Dims& d, const BlockWs& bw, int granularity, int h0, int nh, size_t n_cand,
+                        const void* k, const void* v,
+                        const int32_t* col_idx, const int32_t* col_cnt,
+                        const int32_t* slash_idx, const int32_t* slash_cnt, int32_t local_window,
+                        char* ws, hipStream_t st, const int32_t** cnt_used) {
   const SparseWs& w = bw.sp;
   const bool blocks = granularity != 1;
+  Scope sc(SA_K_MASK_PREP, st);
+  // this pass's rows of the caller's lists
+  col_idx += (size_t)h0 * n_cand; slash_idx += (size_t)h0 * n_cand;
+  col_cnt += h0; slash_cnt += h0;
   sa_status s = SA_OK;
-  sa::MaskPrepParams M;
-  {
-    Scope sc(SA_K_MASK_PREP, st);
+  uint32_t* col_bits = reinterpret_cast<uint32_t*>(ws + w.cbits);
+  uint32_t* off_bits = reinterpret_cast<uint32_t*>(ws + w.obits);
+  int32_t* dlist = reinterpret_cast<int32_t*>(ws + w.dlist);
+  int32_t* dcnt = reinterpret_cast<int32_t*>(ws + w.dcnt);
+  if (!blocks) {
+    // slash side: bitmaps of kept columns / offsets and touched tile diagonals
+    sa::MaskPrepParams M;
     memset(&M, 0, sizeof(M));
-    M.col_bits = reinterpret_cast<uint32_t*>(ws + w.cbits);
-    M.off_bits = reinterpret_cast<uint32_t*>(ws + w.obits);
-    M.dlist = reinterpret_cast<int32_t*>(ws + w.dlist);
-    M.dcnt = reinterpret_cast<int32_t*>(ws + w.dcnt);
-    if (!blocks) {
-      // merge_index, slash side: bitmaps of kept columns / offsets and touched tile diagonals
-      M.col_idx = col_idx; M.col_cnt = col_cnt; M.slash_idx = slash_idx; M.slash_cnt = slash_cnt;
-      M.n_bh = d.n_bh; M.S = d.S; M.window = local_window;
-      M.cb_words = w.cb_words; M.rb_words = w.rb_words; M.dlist_stride = w.dlist_stride; M.off_max = w.off_max;
-      s = dev(sa::launch_mask_prep(M, st));
-    } else {
-      // the same metadata from block lists; from here on the selected key blocks are
-      // the token columns they hold
-      sa::BlockPrepParams B;
-      memset(&B, 0, sizeof(B));
-      B.col_blk = col_idx; B.col_bcnt = col_cnt; B.slash_blk = slash_idx; B.slash_bcnt = slash_cnt;
-      B.tok_idx = reinterpret_cast<int32_t*>(ws + bw.tok_idx);
-      B.tok_cnt = reinterpret_cast<int32_t*>(ws + bw.tok_cnt);
-      B.diag_bits = reinterpret_cast<uint32_t*>(ws + bw.dbits);
-      B.col_bits = M.col_bits; B.off_bits = M.off_bits; B.dlist = M.dlist; B.dcnt = M.dcnt;
-      B.n_bh = d.n_bh; B.S = d.S; B.window = local_window;
-      B.cb_words = w.cb_words; B.rb_words = w.rb_words; B.dlist_stride = w.dlist_stride; B.off_max = w.off_max;
-      B.blk = granularity; B.nb = bw.nb; B.db_words = bw.db_words;
-      s = dev(sa::launch_block_prep(B, st));
-      col_idx = B.tok_idx; col_cnt = B.tok_cnt;
-    }
-    if (s != SA_OK) return s;
-
-    // V^T for the contiguous (slash / window) tiles: once per call
-    if (first_segment) s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + w.vt), st));
-    if (s != SA_OK) return s;
-
-    // merge_index, column side: compact K rows and V^T columns of the kept keys, per query head
-    sa::GatherParams G;
-    memset(&G, 0, sizeof(G));
-    G.idx = col_idx; G.cnt = col_cnt; G.idx_stride = d.S;
-    G.idx_pad = reinterpret_cast<int32_t*>(ws + w.cidx); G.idx_pad_stride = d.S_pad;
-    G.n_out = d.n_bh; G.group = d.group; G.S = d.S; G.C_pad = d.S_pad;
-    G.src = static_cast<const uint16_t*>(v);
-    G.out_t = reinterpret_cast<uint16_t*>(ws + w.vct);
-    s = dev(sa::launch_gather_transpose(G, st));
-    if (s != SA_OK) return s;
-    // K rows: gather only
-    G.src = static_cast<const uint16_t*>(k);
-    G.out_rows = reinterpret_cast<uint16_t*>(ws + w.kc);
-    G.out_t = nullptr;
-    G.idx_pad = nullptr;
-    s = dev(sa::launch_gather_transpose(G, st));
-    if (s != SA_OK) return s;
+    M.col_bits = col_bits; M.off_bits = off_bits; M.dlist = dlist; M.dcnt = dcnt;
+    M.col_idx = col_idx; M.col_cnt = col_cnt; M.slash_idx = slash_idx; M.slash_cnt = slash_cnt;
+    M.n_bh = nh; M.S = d.S; M.window = local_window;
+    M.cb_words = w.cb_words; M.rb_words = w.rb_words; M.dlist_stride = w.dlist_stride; M.off_max = w.off_max;
+    s = dev(sa::launch_mask_prep(M, st));
+  } else {
+    // the same metadata from block lists; from here on the selected key blocks are
+    // the token columns they hold
+    sa::BlockPrepParams B;
+    memset(&B, 0, sizeof(B));
+    B.col_blk = col_idx; B.col_bcnt = col_cnt; B.slash_blk = slash_idx; B.slash_bcnt = slash_cnt;
+    B.tok_idx = reinterpret_cast<int32_t*>(ws + bw.tok_idx);
+    B.tok_cnt = reinterpret_cast<int32_t*>(ws + bw.tok_cnt);
+    B.diag_bits = reinterpret_cast<uint32_t*>(ws + bw.dbits);
+    B.col_bits = col_bits; B.off_bits = off_bits; B.dlist = dlist; B.dcnt = dcnt;
+    B.n_bh = nh; B.S = d.S; B.window = local_window;
+    B.cb_words = w.cb_words; B.rb_words = w.rb_words; B.dlist_stride = w.dlist_stride; B.off_max = w.off_max;
+    B.blk = granularity; B.nb = bw.nb; B.db_words = bw.db_words;
+    s = dev(sa::launch_block_prep(B, st));
+    col_idx = B.tok_idx; col_cnt = B.tok_cnt;
   }
+  if (s != SA_OK) return s;
+  *cnt_used = col_cnt;
+
+  // column side: compact K rows and V^T columns of the kept keys, per query head
+  sa::GatherParams G;
+  memset(&G, 0, sizeof(G));
+  G.idx = col_idx; G.cnt = col_cnt; G.idx_stride = d.S;
+  G.idx_pad = reinterpret_cast<int32_t*>(ws + w.cidx); G.idx_pad_stride = d.S_pad;
+  G.n_out = nh; G.group = d.group; G.head0 = h0; G.S = d.S; G.C_pad = d.S_pad;
+  G.src = static_cast<const uint16_t*>(v);
+  G.out_t = reinterpret_cast<uint16_t*>(ws + w.vct);
+  s = dev(sa::launch_gather_transpose(G, st));
+  if (s != SA_OK) return s;
+  // K rows: gather only
+  G.src = static_cast<const uint16_t*>(k);
+  G.out_rows = reinterpret_cast<uint16_t*>(ws + w.kc);
+  G.out_t = nullptr;
+  G.idx_pad = nullptr;
+  return dev(sa::launch_gather_transpose(G, st));
+}
+
+// the strip-masked kernel on query tiles [qtile0, qtile0 + n_qtiles) of the heads [h0, h0 + nh)
+sa_status launch_attend(const Dims& d, const SparseWs& w, int h0, int nh, int qtile0, int n_qtiles,
+                        const void* q, const void* k, const int32_t* col_cnt,
+                        void* out, int out_dtype, float* out_lse, uint64_t* tiles, char* ws, hipStream_t st) {
   sa::FlashParams P = base_flash(d, q, k);
+  const size_t head_elems = (size_t)d.S * sa::kHeadDim;
+  P.q = static_cast<const uint16_t*>(q) + (size_t)h0 * head_elems;
+  P.out = static_cast<char*>(out) + (size_t)h0 * head_elems * (out_dtype == SA_OUT_F32 ? 4 : 2);
+  P.lse = out_lse ? out_lse + (size_t)h0 * d.S : nullptr;
+  P.tiles = tiles ? reinterpret_cast<unsigned long long*>(tiles) + h0 : nullptr;
+  P.n_bh = nh; P.head0 = h0;
   P.qtile0 = qtile0;
   P.n_qtiles = n_qtiles;
   P.vt = reinterpret_cast<const uint16_t*>(ws + w.vt);
-  P.out = out; P.lse = out_lse;
   P.kc = reinterpret_cast<const uint16_t*>(ws + w.kc);
   P.vct = reinterpret_cast<const uint16_t*>(ws + w.vct);
   P.col_idx_pad = reinterpret_cast<const int32_t*>(ws + w.cidx);
   P.col_cnt = col_cnt;
-  P.col_bits = M.col_bits; P.off_bits = M.off_bits;
-  P.dlist = M.dlist; P.dcnt = M.dcnt;
-  P.tiles = reinterpret_cast<unsigned long long*>(tiles);
+  P.col_bits = reinterpret_cast<const uint32_t*>(ws + w.cbits);
+  P.off_bits = reinterpret_cast<const uint32_t*>(ws + w.obits);
+  P.dlist = reinterpret_cast<const int32_t*>(ws + w.dlist);
+  P.dcnt = reinterpret_cast<const int32_t*>(ws + w.dcnt);
   P.cidx_stride = d.S_pad; P.cb_words = w.cb_words; P.rb_words = w.rb_words;
   P.dlist_stride = w.dlist_stride; P.off_max = w.off_max;
   Scope sc(SA_K_SPARSE_FLASH, st);
   return dev(sa::launch_flash(2, out_dtype == SA_OUT_F32, P, st));
 }
 
-// Argument checks, then one pass per chunk: the lists selected from chunk m mask the
+// Argument checks, then the passes.  Chunks: the lists selected from chunk m mask the
 // query rows of segment m (merge_index with itv = S / chunk_n); a single chunk is the
-// whole matrix.
-sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
+// whole matrix.  Partition (Sec. 5.4, long sequences): the heads are taken
+// heads_per_pass at a time - the workspace holds the metadata and the gathered K / V
+// of one pass only - and the query tiles of a chunk in n_segments consecutive launches.
+// Every (head, query tile) is computed by one workgroup whatever the partition, so the
+// result does not depend on it.
+sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity, const sa_partition* part,
                       const void* q, const void* k, const void* v,
                       const int32_t* col_idx_all, const int32_t* col_cnt_all,
                       const int32_t* slash_idx_all, const int32_t* slash_cnt_all,
@@ -495,13 +521,18 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
   if (s != SA_OK) return s;
   s = check_chunks(d, n_chunks, granularity);
   if (s != SA_OK) return s;
+  int heads_per_pass = d.n_bh, n_segments = 1;
+  if (part != nullptr) {
+    s = check_partition(part, d, &heads_per_pass, &n_segments);
+    if (s != SA_OK) return s;
+  }
   const bool blocks = granularity != 1;
   if (q == nullptr || k == nullptr || v == nullptr || out == nullptr || col_idx_all == nullptr ||
       col_cnt_all == nullptr || slash_idx_all == nullptr || slash_cnt_all == nullptr)
     return SA_ERR_INVALID_ARG;
   if (local_window < 1) return SA_ERR_INVALID_ARG;
   if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
-  const BlockWs bw = block_ws(d, blocks ? granularity : 64);
+  const BlockWs bw = block_ws(d, blocks ? granularity : 64, heads_per_pass);
   s = check_ws(workspace, workspace_bytes, blocks ? bw.total : bw.sp.total);
   if (s != SA_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -510,16 +541,34 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity,
     s = dev(sa::launch_fill_u32(reinterpret_cast<uint32_t*>(tiles), 2 * (size_t)d.n_bh, 0u, st));
     if (s != SA_OK) return s;
   }
+  {
+    // V^T for the contiguous (slash / window) tiles: once per call
+    Scope sc(SA_K_TRANSPOSE_V, st);
+    s = dev(transpose_v(d, v, reinterpret_cast<uint16_t*>(ws + bw.sp.vt), st));
+    if (s != SA_OK) return s;
+  }
   const size_t n_cand = (size_t)(d.S + granularity - 1) / granularity;   // list capacity per head
   const int n_qtiles_all = (d.S + sa::kFlashBQ - 1) / sa::kFlashBQ;
   for (int m = 0; m < n_chunks; ++m) {
     const int qtile0 = (int)((long long)n_qtiles_all * m / n_chunks);
     const int qtile1 = (int)((long long)n_qtiles_all * (m + 1) / n_chunks);
-    s = attend_segment(d, bw, granularity, m == 0, qtile0, qtile1 - qtile0, q, k, v,
-                       col_idx_all + (size_t)m * d.n_bh * n_cand, col_cnt_all + (size_t)m * d.n_bh,
-                       slash_idx_all + (size_t)m * d.n_bh * n_cand, slash_cnt_all + (size_t)m * d.n_bh,
-                       local_window, out, out_dtype, out_lse, tiles, ws, st);
-    if (s != SA_OK) return s;
+    const size_t chunk_off = (size_t)m * d.n_bh;
+    for (int h0 = 0; h0 < d.n_bh; h0 += heads_per_pass) {
+      const int nh = (d.n_bh - h0 < heads_per_pass) ? d.n_bh - h0 : heads_per_pass;
+      const int32_t* cnt_used = nullptr;
+      s = prepare_heads(d, bw, granularity, h0, nh, n_cand, k, v,
+                        col_idx_all + chunk_off * n_cand, col_cnt_all + chunk_off,
+                        slash_idx_all + chunk_off * n_cand, slash_cnt_all + chunk_off,
+                        local_window, ws, st, &cnt_used);
+      if (s != SA_OK) return s;
+      const int segs = (n_segments < qtile1 - qtile0) ? n_segments : (qtile1 - qtile0);
+      for (int g = 0; g < segs; ++g) {
+        const int a0 = qtile0 + (int)((long long)(qtile1 - qtile0) * g / segs);
+        const int a1 = qtile0 + (int)((long long)(qtile1 - qtile0) * (g + 1) / segs);
+        s = launch_attend(d, bw.sp, h0, nh, a0, a1 - a0, q, k, cnt_used, out, out_dtype, out_lse, tiles, ws, st);
+        if (s != SA_OK) return s;
+      }
+    }
   }
   return SA_OK;
 }
@@ -533,8 +582,27 @@ sa_status sa_sparse_attn(const sa_shape* shape, const void* q, const void* k, co
                          int32_t local_window,
                          void* out, int out_dtype, float* out_lse, uint64_t* tiles,
                          void* workspace, size_t workspace_bytes, void* stream) {
-  return sparse_attn(shape, 1, 1, q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window, out, out_dtype,
-                     out_lse, tiles, workspace, workspace_bytes, stream);
+  return sparse_attn(shape, 1, 1, nullptr, q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window, out,
+                     out_dtype, out_lse, tiles, workspace, workspace_bytes, stream);
+}
+
+size_t sa_partitioned_workspace_bytes(const sa_shape* shape, const sa_partition* partition) {
+  Dims d;
+  int hpp = 0, segs = 0;
+  if (check_shape(shape, &d) != SA_OK || check_partition(partition, d, &hpp, &segs) != SA_OK) return 0;
+  return sparse_ws(d, hpp).total;
+}
+
+sa_status sa_sparse_attn_partitioned(const sa_shape* shape, const sa_partition* partition,
+                                     const void* q, const void* k, const void* v,
+                                     const int32_t* col_idx, const int32_t* col_cnt,
+                                     const int32_t* slash_idx, const int32_t* slash_cnt,
+                                     int32_t local_window,
+                                     void* out, int out_dtype, float* out_lse, uint64_t* tiles,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (partition == nullptr) return SA_ERR_INVALID_ARG;
+  return sparse_attn(shape, 1, 1, partition, q, k, v, col_idx, col_cnt, slash_idx, slash_cnt, local_window, out,
+                     out_dtype, out_lse, tiles, workspace, workspace_bytes, stream);
 }
 
 sa_status sa_block_sparse_attn(const sa_shape* shape, int32_t granularity,
@@ -546,7 +614,7 @@ sa_status sa_block_sparse_attn(const sa_shape* shape, int32_t granularity,
                                void* workspace, size_t workspace_bytes, void* stream) {
   if (granularity < 1) return SA_ERR_INVALID_ARG;
   if (granularity == 1) return SA_ERR_UNSUPPORTED;   // per-token strips are sa_sparse_attn
-  return sparse_attn(shape, 1, granularity, q, k, v, col_blocks, col_cnt, slash_blocks, slash_cnt, local_window, out,
+  return sparse_attn(shape, 1, granularity, nullptr, q, k, v, col_blocks, col_cnt, slash_blocks, slash_cnt, local_window, out,
                      out_dtype, out_lse, tiles, workspace, workspace_bytes, stream);
 }
 
@@ -558,8 +626,9 @@ sa_status sa_sparse_attn_chunked(const sa_shape* shape, const sa_sampling* sampl
                                  void* out, int out_dtype, float* out_lse, uint64_t* tiles,
                                  void* workspace, size_t workspace_bytes, void* stream) {
   if (sampling == nullptr) return SA_ERR_INVALID_ARG;
-  return sparse_attn(shape, sampling->n_chunks, sampling->granularity, q, k, v, col_idx, col_cnt, slash_idx,
-                     slash_cnt, local_window, out, out_dtype, out_lse, tiles, workspace, workspace_bytes, stream);
+  return sparse_attn(shape, sampling->n_chunks, sampling->granularity, nullptr, q, k, v, col_idx, col_cnt,
+                     slash_idx, slash_cnt, local_window, out, out_dtype, out_lse, tiles, workspace, workspace_bytes,
+                     stream);
 }
 
 sa_status sa_dense_attn(const sa_shape* shape, const void* q, const void* k, const void* v,
@@ -609,6 +678,16 @@ sa_status sa_dense_attn_static(const sa_shape* shape, const void* q, const void*
   P.vt = vt; P.out = out; P.lse = out_lse;
   Scope sc(SA_K_DENSE_FLASH, st);
   return dev(sa::launch_flash(0, out_dtype == SA_OUT_F32, P, st));
+}
+
+sa_status sa_probe_mfma(int32_t iters, int32_t waves_per_simd, float* sink, void* stream) {
+  if (iters < 1 || waves_per_simd < 1 || waves_per_simd > 8 || sink == nullptr) return SA_ERR_INVALID_ARG;
+  return dev(sa::launch_probe_mfma(iters, waves_per_simd, sink, static_cast<hipStream_t>(stream)));
+}
+
+sa_status sa_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (src == nullptr || dst == nullptr || bytes % 16 != 0) return SA_ERR_INVALID_ARG;
+  return dev(sa::launch_probe_copy(src, dst, bytes, static_cast<hipStream_t>(stream)));
 }
 
 sa_status sa_profile_enable(int enable) {

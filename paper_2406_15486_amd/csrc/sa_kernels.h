@@ -17,6 +17,8 @@ struct FlashParams {
   float* lse;               // nullable
   int S, S_pad;
   int n_bh, n_bkv, group;   // batch*q-heads, batch*kv-heads, q heads per kv head
+  int head0;                // strip-masked mode: q, out, lse, tiles and the per-head metadata start at this
+                            // (batch*q-)head, n_bh counts the heads of this pass; KV head = (head0 + h) / group
   float scale_log2;         // softmax scale * log2(e)
   int n_qtiles;             // 256-row query tiles to process
   int qtile0;               // strip-masked mode: the first of them (a segment of the queries)
@@ -50,7 +52,8 @@ struct GatherParams {
   uint16_t* out_t;          // [n_out, 128, C_pad]
   uint16_t* out_rows;       // nullable [n_out, C_pad, 128]
   int32_t* idx_pad;         // nullable [n_out, idx_pad_stride]: copy of idx padded with INT_MAX
-  int n_out, group;         // source head of output g is g / group
+  int n_out, group;         // source head of output g is (head0 + g) / group
+  int head0;
   int S, C_pad, idx_stride, idx_pad_stride;
 };
 hipError_t launch_gather_transpose(const GatherParams& P, hipStream_t st);
@@ -95,6 +98,10 @@ hipError_t launch_score_accumulate(const ScoreParams& P, hipStream_t st);
 hipError_t launch_score_finalize(const ScoreParams& P, hipStream_t st);
 size_t score_partial_floats(int S, int n_s, int n_bh);
 void score_geometry(int S, int n_s, int* n_kblocks, int* n_chunks, int* chunk_rows, int* win);
+
+// measurement aids: back-to-back MFMA loop and plain copy
+hipError_t launch_probe_mfma(int iters, int waves_per_simd, float* sink, hipStream_t st);
+hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 
 struct SelectParams {
   const float* scores;      // [n_prob, S]

@@ -124,7 +124,9 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
     first[r] = (ql >= e) ? 1.f : 0.f;
     second[r] = 1.f - first[r];
   }
-  // add class C (held in dacc[C]) into the window at block position bpos, and clear it
+  // add class C (held in dacc[C]) into the window at block position bpos.  The
+  // registers are not cleared: the first tile of the next class to use them (always a
+  // sub-block-0 tile) assigns instead of adding.
   auto flush_class = [&](f32x16& acc, int bpos) {
     float a1 = 0.f, a2 = 0.f;
 #pragma unroll
@@ -132,7 +134,6 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
       float v = __int_as_float(__builtin_amdgcn_ds_bpermute(pull[r], __float_as_int(acc[r])));
       a1 = fmaf(v, first[r], a1);
       a2 = fmaf(v, second[r], a2);
-      acc[r] = 0.f;
     }
     volatile lds_f32* s1 = (volatile lds_f32*)(mywin + 32 * bpos);
     *s1 = *s1 + a1;
@@ -193,10 +194,15 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           csum += p[r];
-          dacc[(PAR + sb) & 1][r] += p[r];
+          // tile (b, 0) opens class b, tile (b, 1) completes class b - 1
+          if (sb == 0) dacc[PAR & 1][r] = p[r]; else dacc[(PAR + 1) & 1][r] += p[r];
         }
         colacc[sb] += csum;
       }
+    } else {
+      // no row of the block reaches this wave's keys yet: class b opens empty
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dacc[PAR & 1][r] = 0.f;
     }
     // class b - 1 (tiles (b-1, 0) and (b, 1)) is complete: add it into the window
     flush_class(dacc[(PAR + 1) & 1], b);       // window position 32 * ((b - 1) + 1)

@@ -37,6 +37,7 @@ constexpr int NW = NT / 64;
 constexpr int kCopies = 32;                 // copies of every histogram bin
 constexpr int kCntShift = 43;               // packed bin: count << 43 | mantissa sum (2^24 candidates at most:
                                             // a copy sees 2^19 of them, mantissa sum < 2^42, count < 2^20)
+constexpr int kBatch = 16;                  // scores a lane requests before it uses the first
 constexpr size_t kSelectLds = 256 * kCopies * sizeof(unsigned long long);
 
 // the bit pattern a score is ranked by: negative, infinite and NaN scores carry no
@@ -86,12 +87,23 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
     __syncthreads();
     const unsigned int prefix = sh_prefix;
     unsigned long long* my_hist = hist + (lane & (kCopies - 1));
-    for (int g = g_lo; g < g_hi; ++g) {
-      const int i = g * 64 + lane;
-      const unsigned int key = (i < S) ? score_key(sc[i]) : 0u;
-      const bool live = (i < S) && (pass == 0 || (key >> above_shift) == (prefix >> above_shift));
-      const unsigned int b = (key >> shift) & dmask;
-      if (live) atomicAdd(my_hist + b * kCopies, (1ull << kCntShift) | (unsigned long long)(key & 0x7FFFFFu));
+    // kBatch loads in flight per lane: a wave that waits for every score before it asks
+    // for the next spends the pass waiting
+    for (int g0 = g_lo; g0 < g_hi; g0 += kBatch) {
+      float v[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int i = (g0 + u) * 64 + lane;
+        v[u] = (g0 + u < g_hi && i < S) ? sc[i] : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const unsigned int key = score_key(v[u]);
+        const bool in = g0 + u < g_hi && (g0 + u) * 64 + lane < S;
+        const bool live = in && (pass == 0 || (key >> above_shift) == (prefix >> above_shift));
+        const unsigned int b = (key >> shift) & dmask;
+        if (live) atomicAdd(my_hist + b * kCopies, (1ull << kCntShift) | (unsigned long long)(key & 0x7FFFFFu));
+      }
     }
     __syncthreads();
     if (tid < 256) {
@@ -162,11 +174,20 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
   const unsigned int m = sh_m;
   const unsigned long long lt = (1ull << lane) - 1ull;
   unsigned int n_gt = 0u, n_tie = 0u;
-  for (int g = g_lo; g < g_hi; ++g) {
-    const int i = g * 64 + lane;
-    const unsigned int key = (i < S) ? score_key(sc[i]) : 0u;
-    n_gt += (unsigned int)__popcll(__ballot((i < S) && key > vkey));
-    n_tie += (unsigned int)__popcll(__ballot((i < S) && key == vkey));
+  for (int g0 = g_lo; g0 < g_hi; g0 += kBatch) {
+    float v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = (g0 + u) * 64 + lane;
+      v[u] = (g0 + u < g_hi && i < S) ? sc[i] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const unsigned int key = score_key(v[u]);
+      const bool in = g0 + u < g_hi && (g0 + u) * 64 + lane < S;
+      n_gt += (unsigned int)__popcll(__ballot(in && key > vkey));
+      n_tie += (unsigned int)__popcll(__ballot(in && key == vkey));
+    }
   }
   if (lane == 0) { w_gt[wave] = n_gt; w_tie[wave] = n_tie; }
   __syncthreads();
@@ -177,18 +198,28 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectParams P) {
     pos_run += w_gt[w] + kept_ties;
     tie_run += t;
   }
-  for (int g = g_lo; g < g_hi; ++g) {
-    const int i = g * 64 + lane;
-    const unsigned int key = (i < S) ? score_key(sc[i]) : 0u;
-    const bool gt = (i < S) && key > vkey;
-    const bool tie = (i < S) && key == vkey;
-    const unsigned long long bt = __ballot(tie);
-    const unsigned int trank = tie_run + (unsigned int)__popcll(bt & lt);
-    const bool sel = gt || (tie && trank < m);
-    const unsigned long long bs = __ballot(sel);
-    if (sel) idx[pos_run + (unsigned int)__popcll(bs & lt)] = i;
-    tie_run += (unsigned int)__popcll(bt);
-    pos_run += (unsigned int)__popcll(bs);
+  for (int g0 = g_lo; g0 < g_hi; g0 += kBatch) {
+    float v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = (g0 + u) * 64 + lane;
+      v[u] = (g0 + u < g_hi && i < S) ? sc[i] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int i = (g0 + u) * 64 + lane;
+      const unsigned int key = score_key(v[u]);
+      const bool in = g0 + u < g_hi && i < S;
+      const bool gt = in && key > vkey;
+      const bool tie = in && key == vkey;
+      const unsigned long long bt = __ballot(tie);
+      const unsigned int trank = tie_run + (unsigned int)__popcll(bt & lt);
+      const bool sel = gt || (tie && trank < m);
+      const unsigned long long bs = __ballot(sel);
+      if (sel) idx[pos_run + (unsigned int)__popcll(bs & lt)] = i;
+      tie_run += (unsigned int)__popcll(bt);
+      pos_run += (unsigned int)__popcll(bs);
+    }
   }
   if (wave == NW - 1 && lane == 0) *cnt_out = (int)pos_run;
 }

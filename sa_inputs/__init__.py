@@ -8,6 +8,7 @@ oracle's tests and the GPU path's tests/bench may share.
 """
 from .generator import (  # noqa: F401
     CONFIGS,
+    HEAD_PATTERNS,
     Workload,
     bf16_bits_to_f32,
     f32_to_bf16_bits,

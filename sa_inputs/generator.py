@@ -102,6 +102,19 @@ CONFIGS: Dict[str, Workload] = {
     ),
 }
 
+# Heads of one pattern each (the three kinds of heads the paper's attention maps
+# show): strong planted columns and no diagonal structure, planted diagonals and no
+# sinks, and both.  Same shape and recipe as the 128K workload; ``.scaled(S)`` gives
+# the same heads at another length.  The sinks are given five times the literal gain,
+# so that they carry most of the mass and the head really is a column head.
+HEAD_PATTERNS: Dict[str, Workload] = {
+    "column": Workload("head-column", 11, 131072, 32, 2, n_sinks=32, n_slash=0, window=128,
+                       sink_gain=20.0, q_bias=7.5),
+    "slash": Workload("head-slash", 12, 131072, 32, 2, n_sinks=0, n_slash=2, window=128),
+    "composed": Workload("head-composed", 13, 131072, 32, 2, n_sinks=32, n_slash=2, window=128,
+                         sink_gain=20.0, q_bias=7.5),
+}
+
 
 def rows_from_ratio(seq_len: int, ratio: float) -> int:
     """Sampled-row count: 64 * ceil(ratio * S / 64), clamped to [min(64,S), S]."""

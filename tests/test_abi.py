@@ -207,6 +207,31 @@ def test_chunked_entry_points_validation(lib, B):
     assert attn(B._CSampling(0, 2, 128)) == SA_WORKSPACE
 
 
+def test_partitioned_entry_point_validation(lib, B):
+    sh = _shape(B, n_q_heads=8, seq_len=4096)
+    full = lib.sa_workspace_bytes(2, ctypes.byref(sh), None)
+
+    def need(hpp, segs):
+        return lib.sa_partitioned_workspace_bytes(ctypes.byref(sh), ctypes.byref(B._CPartition(hpp, segs)))
+
+    assert need(0, 1) == 0 and need(1, 0) == 0
+    assert lib.sa_partitioned_workspace_bytes(ctypes.byref(sh), None) == 0
+    assert need(8, 1) == full and need(100, 7) == full            # clamped to the number of heads
+    assert need(2, 1) < need(4, 1) < full
+    per_head = (need(4, 1) - need(2, 1)) // 2
+    assert 4096 * 516 <= per_head <= 4096 * 560                   # gathered K, V^T, index list, bitmaps
+
+    def call(part, ws_bytes=16):
+        return lib.sa_sparse_attn_partitioned(ctypes.byref(sh), ctypes.byref(part) if part is not None else None,
+                                              FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, FAKE, 0, None, None,
+                                              FAKE, ws_bytes, None)
+
+    assert call(None) == SA_INVALID
+    assert call(B._CPartition(0, 1)) == SA_INVALID
+    assert call(B._CPartition(2, -1)) == SA_INVALID
+    assert call(B._CPartition(2, 4)) == SA_WORKSPACE
+
+
 def test_static_scratch_entry_point_limit(lib, B):
     """sa_dense_attn_static keeps V^T in a 16 MiB static device array: a shape that needs
     more is refused before anything is launched."""

@@ -241,3 +241,28 @@ def test_glm1m_long_config():
     of two heads, one per KV head).  Input generation takes a minute or two on the
     host; it reports every finished head."""
     _run_full("glm1m", 0.95, score_heads=[], attn_heads=[2, 27], n_rows=128, lse_rows=8)
+
+
+def test_glm32k_partitioned_by_head_and_query_segment():
+    """The long-sequence scheme (heads a few at a time, queries in segments) on the 32K
+    configuration: bit-identical to the unsplit call, with a fraction of its workspace."""
+    import paper_2406_15486_amd as sa
+    wl = CONFIGS["glm32k"]
+    S, Hq, Hkv, n_s, w = wl.seq_len, wl.n_q_heads, wl.n_kv_heads, wl.n_sample_rows, wl.window
+    _say(f"glm32k partitioned: generating inputs S={S}")
+    x = make_inputs(wl)
+    q, k, v = _dev(x["q"]), _dev(x["k"]), _dev(x["v"])
+    sh = sa.Shape(1, Hq, Hkv, S)
+    col, slash = sa.sa_sample_scores(q, k, n_s)
+    ci, cc, si, sc = sa.sa_select_strips(col, slash, 0.95, 0.9, sh)
+    want, want_lse, want_tiles = sa.sa_sparse_attn(q, k, v, ci, cc, si, sc, w, want_lse=True, want_tiles=True)
+    full = sa.sa_workspace_bytes(sa.binding.SA_OP_SPARSE_ATTN, sh)
+    for hpp, segs in ((4, 1), (5, 3), (1, 128), (32, 2)):
+        need = sa.sa_partitioned_workspace_bytes(sh, hpp, segs)
+        got, lse, tiles = sa.sa_sparse_attn_partitioned(q, k, v, ci, cc, si, sc, w, hpp, segs,
+                                                        want_lse=True, want_tiles=True)
+        torch.cuda.synchronize()
+        _say(f"   heads per pass {hpp}, query segments {segs}: workspace {need / 2**20:.0f} MiB of {full / 2**20:.0f}")
+        assert torch.equal(got, want), (hpp, segs)
+        assert torch.equal(lse, want_lse) and torch.equal(tiles, want_tiles), (hpp, segs)
+        assert need <= full and (hpp >= 32 or need < full * (hpp + 3) / 32)

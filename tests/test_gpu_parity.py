@@ -379,6 +379,32 @@ def test_batch_of_two_sequences(blk):
     _check_out(dense[1, 3].float().cpu().numpy(), want, "batch dense b1 h3")
 
 
+def test_partitioned_sparse_attn_across_batches():
+    """Head partition with a pass that straddles two batch elements (3 heads per pass, 4
+    query heads per sequence, 2 sequences) and query segments on a ragged length."""
+    import paper_2406_15486_amd as sa
+    _say("partitioned sparse attention, batch 2")
+    S, Hq, Hkv, w = 1300, 4, 2, 32
+    xs = [_inputs("glm8k", S=S, Hq=Hq, Hkv=Hkv, seed=s, n_sinks=8)[1] for s in (21, 22)]
+    q = torch.cat([_dev(x["q"]) for x in xs]).contiguous()
+    k = torch.cat([_dev(x["k"]) for x in xs]).contiguous()
+    v = torch.cat([_dev(x["v"]) for x in xs]).contiguous()
+    sh = sa.Shape(2, Hq, Hkv, S)
+    col, slash = sa.sa_sample_scores(q, k, 64)
+    ci, cc, si, sc = sa.sa_select_strips(col, slash, 0.9, 0.8, sh)
+    want, want_lse, want_tiles = sa.sa_sparse_attn(q, k, v, ci, cc, si, sc, w, want_lse=True, want_tiles=True)
+    for hpp, segs in ((3, 2), (1, 1), (8, 100)):
+        got, lse, tiles = sa.sa_sparse_attn_partitioned(q, k, v, ci, cc, si, sc, w, hpp, segs, want_lse=True,
+                                                        want_tiles=True)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want) and torch.equal(lse, want_lse) and torch.equal(tiles, want_tiles), (hpp, segs)
+    # against the oracle: second sequence, a head of its second KV group
+    x = xs[1]
+    gc, gs = ci[7, :int(cc[7])].cpu().numpy(), si[7, :int(sc[7])].cpu().numpy()
+    ref, _ = O.masked_attn(_f64(x["q"])[3], _f64(x["k"])[1], _f64(x["v"])[1], gc, gs, w)
+    _check_out(got[1, 3].float().cpu().numpy(), ref, "partitioned b1 h3")
+
+
 # ---------------------------------------------------------------- numerics ----
 def _bf16_bits(a):
     """float array -> bf16 bit patterns (round to nearest even), as the generator does."""
