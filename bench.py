@@ -73,6 +73,27 @@ def mask_density(S: int, cols: np.ndarray, offs: np.ndarray, window: int) -> flo
     return float(kept_pairs_per_row(S, cols, offs, window).sum() / (S * (S + 1) / 2.0))
 
 
+def schedule_slots(S: int, cols: np.ndarray, offs: np.ndarray, window: int) -> int:
+    """Wave-tile slots the strip-masked kernel's schedule spends on one head: for every
+    256-row query tile, 8 waves times (64-key tiles of gathered columns at or before its
+    last row + 64-key tiles whose 319 offsets against the tile's rows hold a kept one).
+    A slot is spent whether or not the wave has work on the tile (counting only)."""
+    keep = np.zeros(S, dtype=bool)
+    keep[np.asarray(offs, dtype=np.int64)] = True
+    keep[:window] = True
+    c = np.concatenate([[0], np.cumsum(keep)])
+    nq = (S + 255) // 256
+    nd = (S + 63) // 64 + 3
+    d = np.arange(nd)
+    lo, hi = np.clip(64 * d - 255, 0, S), np.clip(64 * d + 63, -1, S - 1)
+    touched = (c[hi + 1] - c[lo] > 0) & (hi >= lo)
+    n_rng_upto = np.concatenate([[0], np.cumsum(touched)])             # touched diagonals d < x
+    last_row = np.minimum(256 * np.arange(nq) + 255, S - 1)
+    n_col = (np.searchsorted(np.asarray(cols, dtype=np.int64), last_row, side="right") + 63) // 64
+    n_rng = n_rng_upto[np.minimum(4 * np.arange(nq) + 4, nd)]           # diagonals d <= 4 a + 3
+    return int(8 * (n_col.sum() + n_rng.sum()))
+
+
 def touched_block_fraction(S: int, cols: np.ndarray, offs: np.ndarray, window: int, blk: int = 128) -> float:
     """Fraction of the blk x blk blocks of the causal triangle that hold at least one kept
     (query, key) pair for one head - the paper's "ratio of calculated blocks" grid (counting only)."""
@@ -319,6 +340,8 @@ def main() -> int:
     kept_pairs = float(sum(kept_pairs_per_row(S, ci_all[h, :int(cc[h])], si_all[h, :int(sc[h])], w).sum()
                            for h in range(Hq)))
     useful_tflops = 4.0 * 128 * kept_pairs / (flash_ms * 1e-3) / 1e12
+    # slots of the kernel's schedule (busy or idle) against the computed wave tiles
+    slots = float(sum(schedule_slots(S, ci_all[h, :int(cc[h])], si_all[h, :int(sc[h])], w) for h in range(Hq)))
     del ci_all, si_all
     ws_bytes = {"sample_scores": sa.sa_workspace_bytes(sa.binding.SA_OP_SAMPLE_SCORES, shape, n_s),
                 "sparse_attn": sa.sa_workspace_bytes(sa.binding.SA_OP_SPARSE_ATTN, shape),
@@ -498,10 +521,10 @@ def main() -> int:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record()
-            flop = sa.sa_probe_mfma(20000, wps, sink)
+            probe_flop = sa.sa_probe_mfma(20000, wps, sink)
             e1.record()
             torch.cuda.synchronize()
-            peaks[f"mfma_bf16_tflops_{wps}_waves_per_simd"] = flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            peaks[f"mfma_bf16_tflops_{wps}_waves_per_simd"] = probe_flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         sa.sa_probe_copy(src, dst)
@@ -563,6 +586,8 @@ def main() -> int:
                    "ms_per_step": "wall-clock mean over the same steps", "step_ms": step_ms},
         "stage_ms": stage_ms,
         "useful_tflops": useful_tflops,
+        "schedule_slot_fraction": slots / dense_tiles,
+        "idle_slot_share": 1.0 - float(tiles.sum()) / slots,
         "kept_pair_fraction": kept_pairs / (Hq * S * (S + 1) / 2.0),
         "workspace_bytes": ws_bytes,
         "measured_peaks": peaks,

@@ -71,16 +71,14 @@ typedef struct {
 } sa_shape;
 
 /* Stage-1 sampling.  n_sample_rows: the last n rows of the sequence are the
- * sampled queries (Algorithm 1 with chunk_n = 1), 1 <= n <= seq_len and a
- * multiple of 32 unless it equals seq_len.  n_chunks and granularity are the
- * paper's chunk_n and blk.  With n_chunks = C > 1 the queries are cut into C
- * segments of itv = seq_len / C rows and the last n rows of EACH segment are
- * sampled (n <= itv, a multiple of 32); seq_len must then be a multiple of
- * 256 * C (segments end at query-tile boundaries; SA_ERR_UNSUPPORTED
- * otherwise).  granularity 1 keeps scores per key / per offset;
- * 64, 128 or 256 sums them over blocks of that many keys / offsets (multiples
- * of the kernels' 64-key tile that divide their 256-row query tile; the paper
- * uses 128); other values return SA_ERR_UNSUPPORTED. */
+ * sampled queries (Algorithm 1 with chunk_n = 1), 1 <= n <= seq_len.
+ * n_chunks and granularity are the paper's chunk_n and blk.  With n_chunks =
+ * C > 1 the queries are cut into C segments of itv = floor(seq_len / C) rows
+ * (the last segment takes the remainder) and the last n rows of EACH segment
+ * are sampled (n <= itv, C <= seq_len).  granularity 1 keeps scores per key /
+ * per offset; 64, 128 or 256 sums them over blocks of that many keys /
+ * offsets (multiples of the kernels' 64-key tile that divide their 256-row
+ * query tile; the paper uses 128); other values return SA_ERR_UNSUPPORTED. */
 typedef struct {
   int32_t n_sample_rows;
   int32_t n_chunks;
@@ -123,9 +121,10 @@ int32_t sa_rows_from_ratio(int32_t seq_len, float ratio);
  *   col_scores[h, J]   = sum of the per-key scores of keys   [blk*J, blk*J + blk)
  *   slash_scores[h, b] = sum of the per-offset scores of offsets [blk*b, blk*b + blk)
  * With sampling->n_chunks = C > 1 the outputs carry a leading chunk dimension,
- * [C, batch*n_q_heads, n]: chunk m holds the scores of the rows
- * [(m+1)*itv - n_sample_rows, (m+1)*itv), exactly as above (causal: those rows
- * see keys up to their own position); row_lse must then be NULL.
+ * [C, batch*n_q_heads, n]: chunk m holds the scores of the last n_sample_rows
+ * rows of segment m (rows [(m+1)*itv - n_sample_rows, (m+1)*itv); the last
+ * segment ends at seq_len), exactly as above (causal: those rows see keys up to
+ * their own position); row_lse must then be NULL.
  * The sums are formed in a fixed order: repeated calls give identical bits.
  */
 sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
@@ -208,7 +207,8 @@ sa_status sa_block_sparse_attn(const sa_shape* shape, int32_t granularity,
  * every (chunk, head, direction) independently.
  *
  * sa_sparse_attn_chunked: what is selected from chunk m masks the query rows of
- * segment m, [m*itv, (m+1)*itv): for those rows the mask is that of
+ * segment m, [m*itv, (m+1)*itv) with itv = floor(seq_len / C), the last segment
+ * running to seq_len: for those rows the mask is that of
  * sa_sparse_attn (granularity 1) or sa_block_sparse_attn with chunk m's lists.
  * Workspace: that of SA_OP_SPARSE_ATTN or SA_OP_BLOCK_SPARSE_ATTN.  `tiles`
  * counts over all segments.

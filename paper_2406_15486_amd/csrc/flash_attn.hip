@@ -169,7 +169,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   const int i_last_wg = min(i0 + BQ, P.q_row0 + P.n_qrows) - 1;  // last valid row
   const int iw0 = i0 + 32 * wave;                        // first query row of the wave
   const int i_me = iw0 + ql;                             // this lane's query row
-  const bool row_ok = i_me <= i_last_wg;
+  const bool row_ok = i_me <= i_last_wg && (MODE != 2 || i_me >= P.row_lo);
   const int a64 = i0 / BK;   // index of the 64-key tile that holds row i0 (i0 % 256 == 0 in MODE 2)
   const uint16_t* kbase = P.k + (size_t)bkv * S * kHeadDim;
   const uint16_t* vtbase = WITH_V ? P.vt + (size_t)bkv * kHeadDim * P.S_pad : nullptr;

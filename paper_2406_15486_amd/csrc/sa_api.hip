@@ -53,13 +53,9 @@ sa_status check_sampling(const sa_sampling* sm, const Dims& d) {
   if (sm->n_sample_rows < 1 || sm->n_sample_rows > d.S) return SA_ERR_INVALID_ARG;
   if (sm->n_chunks < 1 || sm->granularity < 1) return SA_ERR_INVALID_ARG;
   if (sm->granularity != 1 && check_granularity(sm->granularity) != SA_OK) return SA_ERR_UNSUPPORTED;
-  if (sm->n_chunks > 1) {
-    // segments of itv = S / chunk_n rows, cut at query-tile boundaries
-    if (d.S % (sm->n_chunks * sa::kFlashBQ) != 0) return SA_ERR_UNSUPPORTED;
-    if (sm->n_sample_rows > d.S / sm->n_chunks) return SA_ERR_INVALID_ARG;
-    if (sm->n_sample_rows % 32 != 0) return SA_ERR_INVALID_ARG;
-  }
-  if (sm->n_sample_rows % 32 != 0 && sm->n_sample_rows != d.S) return SA_ERR_INVALID_ARG;
+  if (sm->n_chunks > d.S) return SA_ERR_INVALID_ARG;
+  // segments of itv = floor(S / chunk_n) rows (the last one runs to S): the sampled rows must fit
+  if (sm->n_sample_rows > d.S / sm->n_chunks) return SA_ERR_INVALID_ARG;
   return SA_OK;
 }
 
@@ -74,7 +70,7 @@ sa_status check_ws(const void* ws, size_t have, size_t need) {
 sa_status check_chunks(const Dims& d, int n_chunks, int granularity) {
   if (n_chunks < 1 || granularity < 1) return SA_ERR_INVALID_ARG;
   if (granularity != 1 && check_granularity(granularity) != SA_OK) return SA_ERR_UNSUPPORTED;
-  if (n_chunks > 1 && d.S % (n_chunks * sa::kFlashBQ) != 0) return SA_ERR_UNSUPPORTED;
+  if (n_chunks > d.S) return SA_ERR_INVALID_ARG;
   return SA_OK;
 }
 
@@ -145,6 +141,14 @@ sa_status check_partition(const sa_partition* p, const Dims& d, int* heads_per_p
 }
 
 size_t dense_ws(const Dims& d) { return align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2); }
+
+// rows [*lo, *hi) of query segment m of chunk_n (Algorithm 1: itv = S_q / chunk_n; here
+// itv = floor(S / chunk_n) and the last segment takes the remainder)
+inline void segment_rows(int S, int n_chunks, int m, int* lo, int* hi) {
+  const int itv = S / n_chunks;
+  *lo = m * itv;
+  *hi = (m + 1 < n_chunks) ? (m + 1) * itv : S;
+}
 
 inline sa_status dev(hipError_t e) { return e == hipSuccess ? SA_OK : SA_ERR_DEVICE; }
 
@@ -268,8 +272,10 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   const size_t n_cand = (size_t)(d.S + blk - 1) / blk;       // scores per head and direction
 
   for (int m = 0; m < n_chunks; ++m) {
-    // chunk m: the last n_s rows of the m-th of n_chunks equal query segments
-    const int row_first = (int)((long long)d.S * (m + 1) / n_chunks) - n_s;
+    // chunk m: the last n_s rows of the m-th of n_chunks query segments
+    int seg_lo, seg_hi;
+    segment_rows(d.S, n_chunks, m, &seg_lo, &seg_hi);
+    const int row_first = seg_hi - n_s;
     float* out_col = col_scores + (size_t)m * d.n_bh * n_cand;
     float* out_slash = slash_scores + (size_t)m * d.n_bh * n_cand;
     float* tok_col = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_col) : out_col;
@@ -476,7 +482,7 @@ sa_status prepare_heads(const Dims& d, const BlockWs& bw, int granularity, int h
 
 // the strip-masked kernel on query tiles [qtile0, qtile0 + n_qtiles) of the heads [h0, h0 + nh)
 sa_status launch_attend(const Dims& d, const SparseWs& w, int h0, int nh, int qtile0, int n_qtiles,
-                        const void* q, const void* k, const int32_t* col_cnt,
+                        int row_lo, int row_hi, const void* q, const void* k, const int32_t* col_cnt,
                         void* out, int out_dtype, float* out_lse, uint64_t* tiles, char* ws, hipStream_t st) {
   sa::FlashParams P = base_flash(d, q, k);
   const size_t head_elems = (size_t)d.S * sa::kHeadDim;
@@ -487,6 +493,10 @@ sa_status launch_attend(const Dims& d, const SparseWs& w, int h0, int nh, int qt
   P.n_bh = nh; P.head0 = h0;
   P.qtile0 = qtile0;
   P.n_qtiles = n_qtiles;
+  // only rows [row_lo, row_hi) are computed and written (a query tile that straddles two
+  // segments is visited by both launches, each writing its own rows)
+  P.row_lo = row_lo;
+  P.n_qrows = row_hi;
   P.vt = reinterpret_cast<const uint16_t*>(ws + w.vt);
   P.kc = reinterpret_cast<const uint16_t*>(ws + w.kc);
   P.vct = reinterpret_cast<const uint16_t*>(ws + w.vct);
@@ -548,10 +558,11 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity, cons
     if (s != SA_OK) return s;
   }
   const size_t n_cand = (size_t)(d.S + granularity - 1) / granularity;   // list capacity per head
-  const int n_qtiles_all = (d.S + sa::kFlashBQ - 1) / sa::kFlashBQ;
   for (int m = 0; m < n_chunks; ++m) {
-    const int qtile0 = (int)((long long)n_qtiles_all * m / n_chunks);
-    const int qtile1 = (int)((long long)n_qtiles_all * (m + 1) / n_chunks);
+    int row_lo, row_hi;
+    segment_rows(d.S, n_chunks, m, &row_lo, &row_hi);
+    const int qtile0 = row_lo / sa::kFlashBQ;
+    const int qtile1 = (row_hi + sa::kFlashBQ - 1) / sa::kFlashBQ;    // one past the last tile with a row of the segment
     const size_t chunk_off = (size_t)m * d.n_bh;
     for (int h0 = 0; h0 < d.n_bh; h0 += heads_per_pass) {
       const int nh = (d.n_bh - h0 < heads_per_pass) ? d.n_bh - h0 : heads_per_pass;
@@ -565,7 +576,8 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity, cons
       for (int g = 0; g < segs; ++g) {
         const int a0 = qtile0 + (int)((long long)(qtile1 - qtile0) * g / segs);
         const int a1 = qtile0 + (int)((long long)(qtile1 - qtile0) * (g + 1) / segs);
-        s = launch_attend(d, bw.sp, h0, nh, a0, a1 - a0, q, k, cnt_used, out, out_dtype, out_lse, tiles, ws, st);
+        s = launch_attend(d, bw.sp, h0, nh, a0, a1 - a0, row_lo, row_hi, q, k, cnt_used, out, out_dtype, out_lse,
+                          tiles, ws, st);
         if (s != SA_OK) return s;
       }
     }

@@ -23,6 +23,8 @@ struct FlashParams {
   int n_qtiles;             // 256-row query tiles to process
   int qtile0;               // strip-masked mode: the first of them (a segment of the queries)
   int q_row0, n_qrows;      // first query row and number of rows (sampled rows in mode 1)
+  int row_lo;               // strip-masked mode: rows below it are neither computed for nor written
+                            // (rows [row_lo, n_qrows) of the launch's query tiles are; q_row0 = 0 there)
   int k_splits;             // mode 1: the keys of a query tile are cut into this many workgroups (>= 1);
                             // lse is then [k_splits, n_bh, n_qrows] partial values (launch_lse_combine)
   // strip-masked mode only

@@ -110,9 +110,11 @@ def test_sampling_validation(lib, B):
     assert call(None) == SA_INVALID
     assert call(B._CSampling(0, 1, 1)) == SA_INVALID
     assert call(B._CSampling(1024, 1, 1)) == SA_INVALID                     # more rows than the sequence
-    assert call(B._CSampling(50, 1, 1)) == SA_INVALID                       # not a multiple of 32
-    assert call(B._CSampling(64, 3, 1)) == SA_UNSUPPORTED                   # 512 rows do not split into 3 x 256
+    assert call(B._CSampling(50, 1, 1)) == SA_WORKSPACE                     # any row count is valid; 16 bytes is too small
+    assert call(B._CSampling(64, 3, 1)) == SA_WORKSPACE                     # ragged segments (170 + 170 + 172 rows) are valid
+    assert call(B._CSampling(171, 3, 1)) == SA_INVALID                      # more rows than a segment of floor(512 / 3) holds
     assert call(B._CSampling(288, 2, 1)) == SA_INVALID                      # more rows than a segment holds
+    assert call(B._CSampling(1, 513, 1)) == SA_INVALID                      # more chunks than rows
     assert call(B._CSampling(64, 2, 1)) == SA_WORKSPACE                     # valid; 16 bytes is too small
     assert lib.sa_sample_scores(ctypes.byref(sh), ctypes.byref(B._CSampling(64, 2, 1)), FAKE, FAKE, FAKE, FAKE,
                                 FAKE, FAKE, 1 << 40, None) == SA_UNSUPPORTED   # no row_lse output with chunks
@@ -191,7 +193,7 @@ def test_chunked_entry_points_validation(lib, B):
 
     assert sel(None) == SA_INVALID
     assert sel(B._CSampling(0, 0, 1)) == SA_INVALID
-    assert sel(B._CSampling(0, 3, 1)) == SA_UNSUPPORTED
+    assert sel(B._CSampling(0, 600, 1)) == SA_INVALID                      # more chunks than rows
     assert sel(B._CSampling(0, 2, 100)) == SA_UNSUPPORTED
     assert sel(B._CSampling(0, 2, 1), ac=-1.0) == SA_INVALID
 
@@ -201,7 +203,8 @@ def test_chunked_entry_points_validation(lib, B):
                                           None)
 
     assert attn(None) == SA_INVALID
-    assert attn(B._CSampling(0, 3, 1)) == SA_UNSUPPORTED
+    assert attn(B._CSampling(0, 3, 1)) == SA_WORKSPACE                     # ragged segments are valid
+    assert attn(B._CSampling(0, 600, 1)) == SA_INVALID
     assert attn(B._CSampling(0, 2, 1), window=0) == SA_INVALID
     assert attn(B._CSampling(0, 2, 1)) == SA_WORKSPACE
     assert attn(B._CSampling(0, 2, 128)) == SA_WORKSPACE

@@ -48,3 +48,24 @@ def test_block_mask_density_matches_brute_force(S, blk, w, seed):
             lo, hi = max(blk * (bi - bj) - (blk - 1), 0), blk * (bi - bj) + blk - 1
             kept += bool(bj in Ic or keep_off[lo:hi + 1].any())
     assert bench.block_mask_density(S, Ic, Is, w, blk) == pytest.approx(kept / (nb * (nb + 1) / 2.0), rel=1e-12)
+
+
+@pytest.mark.parametrize("S,seed", [(700, 1), (1024, 2), (2000, 3)])
+def test_schedule_slots_match_brute_force(S, seed):
+    rng = np.random.default_rng(seed)
+    cols = np.sort(rng.choice(S, 150, replace=False))
+    offs = np.sort(rng.choice(S, 6, replace=False))
+    w = 5
+    keep = np.zeros(S, dtype=bool)
+    keep[offs] = True
+    keep[:w] = True
+    slots = 0
+    for a in range((S + 255) // 256):
+        last = min(256 * a + 255, S - 1)
+        n_col = -(-int((cols <= last).sum()) // 64)
+        n_rng = 0
+        for d in range(4 * a + 4):                      # key tile 4 a + 3 - d >= 0
+            lo, hi = max(64 * d - 255, 0), min(64 * d + 63, S - 1)
+            n_rng += bool(lo <= hi and keep[lo:hi + 1].any())
+        slots += 8 * (n_col + n_rng)
+    assert bench.schedule_slots(S, cols, offs, w) == slots

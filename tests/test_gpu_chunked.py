@@ -53,7 +53,9 @@ def _score_tol(got, want, what):
 
 
 @pytest.mark.parametrize("S,Hq,Hkv,C,n_s,blk", [(1024, 2, 1, 2, 64, 1), (3072, 4, 2, 4, 128, 1), (2048, 2, 2, 2, 1024, 1),
-                                                (2048, 2, 1, 4, 128, 128)])
+                                                (2048, 2, 1, 4, 128, 128),
+                                                (1000, 2, 1, 3, 50, 1),      # ragged: segments of 333, 333, 334 rows
+                                                (1901, 2, 2, 2, 77, 128)])   # ragged at block granularity
 def test_chunked_scores_match_oracle(S, Hq, Hkv, C, n_s, blk):
     import paper_2406_15486_amd as sa
     _say(f"chunked scores S={S} Hq={Hq} C={C} n_s={n_s} blk={blk}")
@@ -101,7 +103,9 @@ def test_select_chunked_bit_exact():
 
 
 @pytest.mark.parametrize("S,Hq,Hkv,C,w,blk", [(1024, 2, 1, 2, 64, 1), (3072, 2, 2, 4, 128, 1), (1536, 2, 1, 3, 1, 128),
-                                              (2048, 2, 2, 2, 200, 64)])
+                                              (2048, 2, 2, 2, 200, 64),
+                                              (1000, 2, 1, 3, 16, 1),        # segments end inside query tiles
+                                              (1901, 2, 2, 5, 40, 128), (700, 1, 1, 7, 8, 64)])
 def test_chunked_attn_random_lists(S, Hq, Hkv, C, w, blk):
     import paper_2406_15486_amd as sa
     _say(f"chunked attn random S={S} C={C} w={w} blk={blk}")
@@ -133,7 +137,8 @@ def test_chunked_attn_random_lists(S, Hq, Hkv, C, w, blk):
     assert (tiles.cpu().numpy() > 0).all()
 
 
-@pytest.mark.parametrize("name,S,Hq,Hkv,C,gain,blk", [("glm32k", 2048, 2, 1, 2, 5.0, 1), ("glm32k", 4096, 4, 2, 4, None, 128)])
+@pytest.mark.parametrize("name,S,Hq,Hkv,C,gain,blk", [("glm32k", 2048, 2, 1, 2, 5.0, 1), ("glm32k", 4096, 4, 2, 4, None, 128),
+                                                      ("glm32k", 3001, 2, 1, 3, 5.0, 1)])
 def test_chunked_pipeline_end_to_end(name, S, Hq, Hkv, C, gain, blk):
     import paper_2406_15486_amd as sa
     _say(f"chunked pipeline {name} S={S} C={C} gain={gain} blk={blk}")

@@ -115,6 +115,9 @@ def _score_tol(got, want, what):
     ("glm8k", 2500, 4, 2, 192, None),        # ragged: S not a multiple of 128
     ("glm32k", 4096, 2, 1, 2304, 5.0),       # more than one chunk of sampled rows
     ("tiny", 200, 1, 1, 200, None),          # every row sampled
+    ("glm8k", 777, 2, 1, 50, None),          # a sampled-row count that is no multiple of 32
+    ("glm8k", 1500, 2, 2, 1, None),          # a single sampled row
+    ("glm32k", 3000, 2, 1, 1100, None),      # ragged count, more than one row chunk
 ])
 def test_sample_scores_matches_oracle(name, S, Hq, Hkv, n_s, gain):
     import paper_2406_15486_amd as sa
