@@ -3,7 +3,7 @@
 // tile and accumulate it down the key columns and along the diagonals.
 //
 // One workgroup = 256 keys (4 waves x 64 keys, K resident in registers as two
-// MFMA B operands) x one chunk of sampled rows.  S = Q K^T is formed 32 rows at
+// MFMA B operands), taking the chunks of 1024 sampled rows one after the other.  S = Q K^T is formed 32 rows at
 // a time, so one lane holds ONE key (lane % 32) and 16 query rows: the column
 // sum is in-lane arithmetic.  For the diagonals, the tile (row block b, key
 // sub-block kb) has exactly the lane/register -> diagonal mapping of every other
@@ -42,14 +42,12 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
 
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int ql = lane & 31, hf = lane >> 5;
-  const int kb = blockIdx.x, ch = blockIdx.y, bh = blockIdx.z;
+  const int kb = blockIdx.x, bh = blockIdx.z;
   const int S = P.S;
   const int r0 = P.row_first;                       // sampled rows [r0, r_end)
   const int r_end = r0 + P.n_s;
-  const int row0 = r0 + ch * QC;                    // first row of the chunk
-  const int row_end = min(row0 + QC, r_end);        // one past the last row
   const int j0 = kb * KB;
-  if (row_end - 1 < j0) return;                     // chunk entirely above these keys
+  if (r_end - 1 < j0) return;                       // every sampled row lies above these keys
   const int jw = j0 + 64 * wave;
   const int bkv = bh / P.group;
   const float c2 = P.scale_log2;
@@ -67,17 +65,42 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
       kf[sb][ks] = as_bf16x8(v);
     }
   }
+  const uint16_t* qbase = P.q + (size_t)bh * S * kHeadDim;
+  const float* lbase = P.lse + (size_t)bh * P.n_s;
+  const int qrow_t = tid >> 4, qcol_t = tid & 15;
+  // slot of (row rb + m, key jw + 32 sb + ql) in this wave's window:
+  //   32 (b - sb + 1) + (m - ql) + 31
+  // The class sum.  Register r of lane ql holds the diagonal e(r) - ql, with e(r) =
+  // 8 (r / 4) + r % 4, of 59 in all (-31 .. 27).  Lane L collects diagonal L - 31 (from
+  // the registers with e(r) <= L, lane e(r) + 31 - L) and diagonal L + 1 (from the
+  // others, lane e(r) - 1 - L): for each r one pull from lane (e(r) + 31 - L) mod 32 of
+  // its own half, credited to the one or the other by 0/1 factors (the products are
+  // exact).  Their window slots are 32 b' + L and 32 b' + 32 + L.
+  float* mywin = win + (wave * 2 + hf) * WWIN + ql + 4 * hf;
+  int pull[16];
+  float first[16], second[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int e = 8 * (r >> 2) + (r & 3);
+    pull[r] = 4 * (((e + 31 - ql) & 31) + 32 * hf);
+    first[r] = (ql >= e) ? 1.f : 0.f;
+    second[r] = 1.f - first[r];
+  }
+
+  // The keys stay in registers while the workgroup goes through the chunks of sampled
+  // rows one after the other (each chunk has its own window and its own partial sums).
+  for (int ch = 0; ch < P.n_chunks; ++ch) {
+  const int row0 = r0 + ch * QC;                    // first row of the chunk
+  const int row_end = min(row0 + QC, r_end);        // one past the last row
+  if (row_end - 1 < j0) continue;                   // chunk entirely above these keys (uniform)
   for (int x = tid; x < 8 * WWIN; x += 256) win[x] = 0.f;
 
   // first 32-row block that reaches the keys of the workgroup, rounded down to even
   const int nblk = (row_end - row0 + 31) / 32;
   const int b_first = ((j0 > row0) ? (j0 - row0) / 32 : 0) & ~1;
-  const uint16_t* qbase = P.q + (size_t)bh * S * kHeadDim;
-  const float* lbase = P.lse + (size_t)bh * P.n_s;
 
   uint4 pq0, pq1;
   float pl = 0.f;
-  const int qrow_t = tid >> 4, qcol_t = tid & 15;
   auto load_block = [&](int b) {
     int rb = row0 + 32 * b;
     int i0 = rb + qrow_t, i1 = i0 + 16;
@@ -106,24 +129,6 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
   f32x16 dacc[2];                 // diagonal classes (b - sb) even / odd
 #pragma unroll
   for (int r = 0; r < 16; ++r) { dacc[0][r] = 0.f; dacc[1][r] = 0.f; }
-  // slot of (row rb + m, key jw + 32 sb + ql) in this wave's window:
-  //   32 (b - sb + 1) + (m - ql) + 31
-  // The class sum.  Register r of lane ql holds the diagonal e(r) - ql, with e(r) =
-  // 8 (r / 4) + r % 4, of 59 in all (-31 .. 27).  Lane L collects diagonal L - 31 (from
-  // the registers with e(r) <= L, lane e(r) + 31 - L) and diagonal L + 1 (from the
-  // others, lane e(r) - 1 - L): for each r one pull from lane (e(r) + 31 - L) mod 32 of
-  // its own half, credited to the one or the other by 0/1 factors (the products are
-  // exact).  Their window slots are 32 b' + L and 32 b' + 32 + L.
-  float* mywin = win + (wave * 2 + hf) * WWIN + ql + 4 * hf;
-  int pull[16];
-  float first[16], second[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int e = 8 * (r >> 2) + (r & 3);
-    pull[r] = 4 * (((e + 31 - ql) & 31) + 32 * hf);
-    first[r] = (ql >= e) ? 1.f : 0.f;
-    second[r] = 1.f - first[r];
-  }
   // add class C (held in dacc[C]) into the window at block position bpos.  The
   // registers are not cleared: the first tile of the next class to use them (always a
   // sub-block-0 tile) assigns instead of adding.
@@ -245,6 +250,8 @@ __global__ __launch_bounds__(256, 2) void score_accumulate_kernel(ScoreParams P)
     }
     out[x] = acc;
   }
+  __syncthreads();     // the windows are cleared for the next chunk only after everyone has read them
+  }  // chunks
 }
 
 // col[h][j] = sum over chunks; slash[h][o] = sum over the (key block, chunk)
@@ -312,7 +319,7 @@ hipError_t launch_score_accumulate(const ScoreParams& P0, hipStream_t st) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_accumulate_kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return e;
-  dim3 grid(A.n_kblocks, A.n_chunks, A.n_bh);
+  dim3 grid(A.n_kblocks, 1, A.n_bh);       // a workgroup takes the row chunks in turn
   hipLaunchKernelGGL(score_accumulate_kernel, grid, dim3(256), shmem, st, A);
   return hipGetLastError();
 }
