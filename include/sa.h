@@ -92,7 +92,8 @@ typedef enum {
   SA_OP_SELECT_STRIPS = 1,
   SA_OP_SPARSE_ATTN = 2,
   SA_OP_DENSE_ATTN = 3,
-  SA_OP_BLOCK_SPARSE_ATTN = 4
+  SA_OP_BLOCK_SPARSE_ATTN = 4,
+  SA_OP_SAMPLE_SCORES_MIN = 5 /* the least sa_sample_scores works with */
 } sa_op;
 
 /* Bytes of device workspace `op` needs for this shape (sampling may be NULL
@@ -126,6 +127,12 @@ int32_t sa_rows_from_ratio(int32_t seq_len, float ratio);
  * segment ends at seq_len), exactly as above (causal: those rows see keys up to
  * their own position); row_lse must then be NULL.
  * The sums are formed in a fixed order: repeated calls give identical bits.
+ * Workspace: with sa_workspace_bytes(SA_OP_SAMPLE_SCORES, ..) all heads are
+ * processed at once.  Any smaller size down to SA_OP_SAMPLE_SCORES_MIN is
+ * accepted as well: the heads are then taken as many at a time as fit (whole
+ * KV heads, or an equal part of one KV head's query heads), pass after pass,
+ * with the same result - which bounds the workspace for long sequences (it
+ * grows with seq_len * n_sample_rows per head, Sec. 5.4).
  */
 sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
                            const void* q, const void* k,

@@ -20,6 +20,7 @@ _LIB_NAME = "libsampleattn.so"
 SA_OUT_BF16, SA_OUT_F32 = 0, 1
 SA_OP_SAMPLE_SCORES, SA_OP_SELECT_STRIPS, SA_OP_SPARSE_ATTN, SA_OP_DENSE_ATTN = 0, 1, 2, 3
 SA_OP_BLOCK_SPARSE_ATTN = 4
+SA_OP_SAMPLE_SCORES_MIN = 5
 
 
 class SaError(RuntimeError):
@@ -169,10 +170,11 @@ def n_blocks(seq_len: int, granularity: int) -> int:
     return (seq_len + granularity - 1) // granularity
 
 
-def sa_workspace_bytes(op: int, shape: Shape, n_sample_rows: int = 0, granularity: int = 1) -> int:
+def sa_workspace_bytes(op: int, shape: Shape, n_sample_rows: int = 0, granularity: int = 1,
+                       n_chunks: int = 1) -> int:
     lib = load_library()
     cs = shape.c()
-    sm = _CSampling(n_sample_rows, 1, granularity)
+    sm = _CSampling(n_sample_rows, n_chunks, granularity)
     return int(lib.sa_workspace_bytes(op, ctypes.byref(cs), ctypes.byref(sm)))
 
 

@@ -92,6 +92,27 @@ SampleWs sample_ws(const Dims& d, int n_s, int granularity) {
   return w;
 }
 
+// The heads [h0, h0 + nh) as a problem of their own: nh is a multiple of the heads per KV
+// head (whole KV heads) or divides it (part of one KV head), so that head h of the pass
+// still reads KV head h / group of the pass once the K pointer is moved to the pass's first.
+Dims pass_dims(const Dims& d, int nh) {
+  Dims p = d;
+  p.n_bh = nh;
+  p.n_bkv = nh >= d.group ? nh / d.group : 1;
+  p.group = nh >= d.group ? d.group : nh;
+  return p;
+}
+
+// how many heads one pass of sa_sample_scores may take with `have` bytes of workspace
+int sample_heads_per_pass(const Dims& d, int n_s, int blk, size_t have) {
+  if (sample_ws(d, n_s, blk).total <= have) return d.n_bh;
+  for (int nkv = d.n_bkv - 1; nkv >= 1; --nkv)
+    if (sample_ws(pass_dims(d, nkv * d.group), n_s, blk).total <= have) return nkv * d.group;
+  for (int nh = d.group - 1; nh >= 1; --nh)
+    if (d.group % nh == 0 && sample_ws(pass_dims(d, nh), n_s, blk).total <= have) return nh;
+  return 0;
+}
+
 struct SparseWs {
   size_t vt, kc, vct, cidx, cbits, obits, dlist, dcnt, total;
   int cb_words, rb_words, dlist_stride, off_max;
@@ -231,6 +252,9 @@ size_t sa_workspace_bytes(int op, const sa_shape* shape, const sa_sampling* samp
     case SA_OP_SAMPLE_SCORES:
       if (check_sampling(sampling, d) != SA_OK) return 0;
       return sample_ws(d, sampling->n_sample_rows, sampling->granularity).total;
+    case SA_OP_SAMPLE_SCORES_MIN:
+      if (check_sampling(sampling, d) != SA_OK) return 0;
+      return sample_ws(pass_dims(d, 1), sampling->n_sample_rows, sampling->granularity).total;
     case SA_OP_SELECT_STRIPS: return 0;
     case SA_OP_SPARSE_ATTN: return sparse_ws(d, d.n_bh).total;
     case SA_OP_DENSE_ATTN: return dense_ws(d);
@@ -262,65 +286,75 @@ sa_status sa_sample_scores(const sa_shape* shape, const sa_sampling* sampling,
   const int n_s = sampling->n_sample_rows;
   const int blk = sampling->granularity;
   const int n_chunks = sampling->n_chunks;
-  SampleWs w = sample_ws(d, n_s, blk);
-  s = check_ws(workspace, workspace_bytes, w.total);
-  if (s != SA_OK) return s;
   if (row_lse != nullptr && n_chunks != 1) return SA_ERR_UNSUPPORTED;
+  // all heads at once if the workspace allows, else as many as fit, pass after pass
+  s = check_ws(workspace, workspace_bytes, sample_ws(pass_dims(d, 1), n_s, blk).total);
+  if (s != SA_OK) return s;
+  const int heads_per_pass = sample_heads_per_pass(d, n_s, blk, workspace_bytes);
+  if (heads_per_pass < 1) return SA_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  float* lse = row_lse ? row_lse : reinterpret_cast<float*>(ws + w.lse);
   const size_t n_cand = (size_t)(d.S + blk - 1) / blk;       // scores per head and direction
+  const size_t head_elems = (size_t)d.S * sa::kHeadDim;
 
   for (int m = 0; m < n_chunks; ++m) {
     // chunk m: the last n_s rows of the m-th of n_chunks query segments
     int seg_lo, seg_hi;
     segment_rows(d.S, n_chunks, m, &seg_lo, &seg_hi);
     const int row_first = seg_hi - n_s;
-    float* out_col = col_scores + (size_t)m * d.n_bh * n_cand;
-    float* out_slash = slash_scores + (size_t)m * d.n_bh * n_cand;
-    float* tok_col = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_col) : out_col;
-    float* tok_slash = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_slash) : out_slash;
+    for (int h0 = 0; h0 < d.n_bh; h0 += heads_per_pass) {
+      const int nh = (d.n_bh - h0 < heads_per_pass) ? d.n_bh - h0 : heads_per_pass;
+      const Dims pd = pass_dims(d, nh);
+      const SampleWs w = sample_ws(pd, n_s, blk);
+      const void* q_pass = static_cast<const uint16_t*>(q) + (size_t)h0 * head_elems;
+      const void* k_pass = static_cast<const uint16_t*>(k) + (size_t)(h0 / d.group) * head_elems;
+      float* lse = row_lse ? row_lse + (size_t)h0 * n_s : reinterpret_cast<float*>(ws + w.lse);
+      float* out_col = col_scores + ((size_t)m * d.n_bh + h0) * n_cand;
+      float* out_slash = slash_scores + ((size_t)m * d.n_bh + h0) * n_cand;
+      float* tok_col = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_col) : out_col;
+      float* tok_slash = blk > 1 ? reinterpret_cast<float*>(ws + w.tok_slash) : out_slash;
 
-    // pass 1: log-sum-exp of every sampled row (flash sweep without V)
-    sa::FlashParams P = base_flash(d, q, k);
-    P.k_splits = sa::lse_key_splits(row_first, n_s, d.n_bh);
-    if (P.k_splits > kMaxKeySplits) P.k_splits = kMaxKeySplits;
-    P.lse = P.k_splits > 1 ? reinterpret_cast<float*>(ws + w.lse_part) : lse;
-    P.q_row0 = row_first;
-    P.n_qrows = n_s;
-    P.n_qtiles = (n_s + sa::kFlashBQ - 1) / sa::kFlashBQ;
-    {
-      Scope sc(SA_K_ROW_LSE, st);
-      s = dev(sa::launch_flash(1, false, P, st));
-      if (s == SA_OK && P.k_splits > 1)
-        s = dev(sa::launch_lse_combine(P.lse, lse, (size_t)d.n_bh * n_s, P.k_splits, st));
-    }
-    if (s != SA_OK) return s;
+      // pass 1: log-sum-exp of every sampled row (flash sweep without V)
+      sa::FlashParams P = base_flash(pd, q_pass, k_pass);
+      P.k_splits = sa::lse_key_splits(row_first, n_s, pd.n_bh);
+      if (P.k_splits > kMaxKeySplits) P.k_splits = kMaxKeySplits;
+      P.lse = P.k_splits > 1 ? reinterpret_cast<float*>(ws + w.lse_part) : lse;
+      P.q_row0 = row_first;
+      P.n_qrows = n_s;
+      P.n_qtiles = (n_s + sa::kFlashBQ - 1) / sa::kFlashBQ;
+      {
+        Scope sc(SA_K_ROW_LSE, st);
+        s = dev(sa::launch_flash(1, false, P, st));
+        if (s == SA_OK && P.k_splits > 1)
+          s = dev(sa::launch_lse_combine(P.lse, lse, (size_t)pd.n_bh * n_s, P.k_splits, st));
+      }
+      if (s != SA_OK) return s;
 
-    // pass 2: recompute the probabilities and accumulate columns and diagonals
-    sa::ScoreParams C;
-    memset(&C, 0, sizeof(C));
-    C.q = static_cast<const uint16_t*>(q);
-    C.k = static_cast<const uint16_t*>(k);
-    C.lse = lse;
-    C.col = tok_col; C.slash = tok_slash;
-    C.partial = reinterpret_cast<float*>(ws + w.partial);
-    C.S = d.S; C.n_s = n_s; C.n_bh = d.n_bh; C.n_bkv = d.n_bkv; C.group = d.group;
-    C.row_first = row_first;
-    C.scale_log2 = P.scale_log2;
-    {
-      Scope sc(SA_K_SCORE_ACCUM, st);
-      s = dev(sa::launch_score_accumulate(C, st));
+      // pass 2: recompute the probabilities and accumulate columns and diagonals
+      sa::ScoreParams C;
+      memset(&C, 0, sizeof(C));
+      C.q = static_cast<const uint16_t*>(q_pass);
+      C.k = static_cast<const uint16_t*>(k_pass);
+      C.lse = lse;
+      C.col = tok_col; C.slash = tok_slash;
+      C.partial = reinterpret_cast<float*>(ws + w.partial);
+      C.S = d.S; C.n_s = n_s; C.n_bh = pd.n_bh; C.n_bkv = pd.n_bkv; C.group = pd.group;
+      C.row_first = row_first;
+      C.scale_log2 = P.scale_log2;
+      {
+        Scope sc(SA_K_SCORE_ACCUM, st);
+        s = dev(sa::launch_score_accumulate(C, st));
+      }
+      if (s != SA_OK) return s;
+      {
+        Scope sc(SA_K_SCORE_FINAL, st);
+        s = dev(sa::launch_score_finalize(C, st));
+        // block_reduction: the per-token scores summed over blocks of blk keys / offsets
+        if (s == SA_OK && blk > 1) s = dev(sa::launch_block_reduce(tok_col, out_col, pd.n_bh, d.S, blk, st));
+        if (s == SA_OK && blk > 1) s = dev(sa::launch_block_reduce(tok_slash, out_slash, pd.n_bh, d.S, blk, st));
+      }
+      if (s != SA_OK) return s;
     }
-    if (s != SA_OK) return s;
-    {
-      Scope sc(SA_K_SCORE_FINAL, st);
-      s = dev(sa::launch_score_finalize(C, st));
-      // block_reduction: the per-token scores summed over blocks of blk keys / offsets
-      if (s == SA_OK && blk > 1) s = dev(sa::launch_block_reduce(tok_col, out_col, d.n_bh, d.S, blk, st));
-      if (s == SA_OK && blk > 1) s = dev(sa::launch_block_reduce(tok_slash, out_slash, d.n_bh, d.S, blk, st));
-    }
-    if (s != SA_OK) return s;
   }
   return SA_OK;
 }

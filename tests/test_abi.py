@@ -125,6 +125,18 @@ def test_sampling_validation(lib, B):
     assert call(B._CSampling(64, 1, 1)) == SA_WORKSPACE                     # 16 bytes is too small
 
 
+def test_sample_scores_least_workspace(lib, B):
+    sh = _shape(B, n_q_heads=8, n_kv_heads=2, seq_len=4096)
+    sm = B._CSampling(256, 1, 1)
+    full = lib.sa_workspace_bytes(0, ctypes.byref(sh), ctypes.byref(sm))
+    least = lib.sa_workspace_bytes(5, ctypes.byref(sh), ctypes.byref(sm))
+    assert 0 < least <= full // 7 and least % 256 == 0      # one head of eight
+    assert lib.sa_workspace_bytes(5, ctypes.byref(sh), ctypes.byref(B._CSampling(0, 1, 1))) == 0
+    # a workspace below the least is refused before anything is launched
+    assert lib.sa_sample_scores(ctypes.byref(sh), ctypes.byref(sm), FAKE, FAKE, FAKE, FAKE, None, FAKE,
+                                least - 256, None) == SA_WORKSPACE
+
+
 def test_select_and_sparse_validation(lib, B):
     sh = _shape(B)
 

@@ -139,6 +139,44 @@ def test_sample_scores_matches_oracle(name, S, Hq, Hkv, n_s, gain):
         assert abs(float(slash[h].double().sum()) - n_s) < 1e-3 * n_s
 
 
+def test_sample_scores_with_a_small_workspace_takes_the_heads_in_passes():
+    """Any workspace from SA_OP_SAMPLE_SCORES_MIN up is accepted: the heads are then
+    processed as many at a time as fit.  The split of the keys of the log-sum-exp sweep
+    depends on the number of heads in a launch, so the scores agree to rounding, not bit
+    for bit; both are checked against the oracle's tolerance."""
+    import paper_2406_15486_amd as sa
+    import paper_2406_15486_amd.binding as B
+    _say("sample_scores in head passes")
+    S, Hq, Hkv, n_s = 2300, 8, 2, 160
+    wl, x = _inputs("glm32k", S=S, Hq=Hq, Hkv=Hkv)
+    q, k = _dev(x["q"]), _dev(x["k"])
+    sh = sa.Shape(1, Hq, Hkv, S)
+    full = sa.sa_workspace_bytes(B.SA_OP_SAMPLE_SCORES, sh, n_s)
+    least = sa.sa_workspace_bytes(B.SA_OP_SAMPLE_SCORES_MIN, sh, n_s)
+    assert 0 < least < full / 4
+    col, slash, lse = sa.sa_sample_scores(q, k, n_s, want_lse=True)
+    qf, kf = _f64(x["q"]), _f64(x["k"])
+    for nbytes in (least, least * 2 + 4096, full // 2 + 4096, full - 256):   # 1, 2, 4 heads per pass; 4 again
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        c2, s2, l2 = sa.sa_sample_scores(q, k, n_s, workspace=ws, want_lse=True)
+        torch.cuda.synchronize()
+        assert torch.allclose(c2, col, rtol=2e-5, atol=1e-8) and torch.allclose(s2, slash, rtol=2e-5, atol=1e-8)
+        assert torch.allclose(l2, lse, rtol=0, atol=1e-4)
+        for h in (0, 5, 7):
+            wc, wsl, _ = O.sample_scores(qf[h], kf[h // (Hq // Hkv)], n_s)
+            _score_tol(c2[h].cpu().numpy(), wc, f"col h{h} ws={nbytes}")
+            _score_tol(s2[h].cpu().numpy(), wsl, f"slash h{h} ws={nbytes}")
+    with pytest.raises(sa.SaError):
+        sa.sa_sample_scores(q, k, n_s, workspace=torch.empty(least - 256, dtype=torch.uint8, device="cuda"))
+    # block granularity and chunks go through the same passes
+    cb, sb = sa.sa_sample_scores(q, k, 128, granularity=128, n_chunks=2)
+    ws = torch.empty(sa.sa_workspace_bytes(B.SA_OP_SAMPLE_SCORES_MIN, sh, 128, granularity=128, n_chunks=2),
+                     dtype=torch.uint8, device="cuda")
+    cb2, sb2 = sa.sa_sample_scores(q, k, 128, granularity=128, n_chunks=2, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.allclose(cb2, cb, rtol=2e-5, atol=1e-8) and torch.allclose(sb2, sb, rtol=2e-5, atol=1e-8)
+
+
 # ----------------------------------------------------------------- stage 2 ----
 def _select_case(scores_c, scores_s, alpha_c, alpha_s):
     import paper_2406_15486_amd as sa
