@@ -107,8 +107,13 @@ __device__ __forceinline__ void wg_barrier() {
 }  // namespace
 
 // MODE: 0 dense causal, 1 row log-sum-exp only (no V), 2 strip-masked sparse.
-template <int MODE, bool OUT_F32>
+// IN_PLACE (strip-masked mode, block lists): the gathered-column tiles are runs of 64
+// consecutive keys (blocks of 64, 128 or 256 keys), so they are read from K and V^T
+// themselves instead of from gathered copies; the padded index list still travels with
+// every tile (causal edge, short last block).
+template <int MODE, bool OUT_F32, bool IN_PLACE = false>
 __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashParams P) {
+  static_assert(!IN_PLACE || MODE == 2, "in-place column tiles belong to the strip-masked mode");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr bool WITH_V = (MODE != 1);
   // Where a wave issues its share of the tile loads.  Each direct load stalls the wave
@@ -226,6 +231,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     // runs, and only so does the load stay a scalar one (tracked apart from the vector
     // loads in flight) behind the barriers and inline assembly of the loop
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+    if (IN_PLACE && t < n_col_tiles)
+      return ((const_i32_ptr)(uintptr_t)cidx)[BK * t];                       // first key of the tile's block
     if (MODE == 2 && t >= n_col_tiles && t < n_tiles)
       return ((const_i32_ptr)(uintptr_t)dl)[n_rng - 1 - (t - n_col_tiles)];   // far to near
     return 0;
@@ -233,6 +240,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // kind and first key of tile t (wave-uniform; no memory access)
   auto is_col = [&](int t) -> bool { return MODE == 2 && t < n_col_tiles; };
   auto first_key = [&](int t, int d) -> int {          // contiguous tiles only; d = list entry
+    if (IN_PLACE && t < n_col_tiles) return d;         // the entry of an in-place column tile is its first key
     return (MODE == 2) ? (a64 + 3 - (d & kDiagMask)) * BK : (t + (MODE == 1 ? t_base : 0)) * BK;
   };
   // array bases as scalars, once
@@ -289,7 +297,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // K / V^T, always readable, loaded into the wave's dump kilobyte.
   auto load_v_begin = [&](int t, int d) {
     if (!WITH_V) return;
-    const bool real = t < n_tiles, col = real && is_col(t);
+    const bool real = t < n_tiles, col = !IN_PLACE && real && is_col(t);   // col: from the gathered copy
     const uint32_t off = !real ? 0u : (col ? (uint32_t)t : (uint32_t)first_key(t, d)) * 2u;   // bytes into a V^T row; t * 64 keys for a gathered tile
     ld_vbase = col ? s_vct + (uint64_t)((uint32_t)t * (BK * 2u)) : s_vtbase + off;
     ld_vbase1 = ld_vbase + 128ull * (uint32_t)P.S_pad;            // run w + 8: 64 rows of V^T further on
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     ld_vstep = real ? 8192 : 0;                    // a stand-in tile writes both runs to the same dump kilobyte
   };
   auto load_k_begin = [&](int t, int d) {
-    const bool real = t < n_tiles, col = real && is_col(t);
+    const bool real = t < n_tiles, col = !IN_PLACE && real && is_col(t);
     const int kmax = col ? P.S_pad - 1 : S - 1;    // last row of the array that may be read
     // a range tile may start past the last key (all of it masked): the base row is
     // clamped, and so is each lane's byte offset, to the last row that exists
@@ -796,13 +804,13 @@ int lse_key_splits(int row_first, int n_s, int n_bh) {
   return best;
 }
 
-template <int MODE, bool OUT_F32>
+template <int MODE, bool OUT_F32, bool IN_PLACE = false>
 static hipError_t launch_one(const FlashParams& P, int grid, hipStream_t st) {
   size_t shmem = (MODE == 1) ? LDS_B_LSE : LDS_B;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kernel<MODE, OUT_F32>),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&flash_kernel<MODE, OUT_F32, IN_PLACE>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)shmem);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((flash_kernel<MODE, OUT_F32>), dim3(grid), dim3(NT), shmem, st, P);
+  hipLaunchKernelGGL((flash_kernel<MODE, OUT_F32, IN_PLACE>), dim3(grid), dim3(NT), shmem, st, P);
   return hipGetLastError();
 }
 
@@ -818,7 +826,10 @@ hipError_t launch_flash(int mode, bool out_f32, const FlashParams& P, hipStream_
   switch (mode) {
     case 0: return out_f32 ? launch_one<0, true>(P, grid, st) : launch_one<0, false>(P, grid, st);
     case 1: return launch_one<1, false>(P, grid, st);
-    default: return out_f32 ? launch_one<2, true>(P, grid, st) : launch_one<2, false>(P, grid, st);
+    default:
+      if (P.cols_in_place)
+        return out_f32 ? launch_one<2, true, true>(P, grid, st) : launch_one<2, false, true>(P, grid, st);
+      return out_f32 ? launch_one<2, true>(P, grid, st) : launch_one<2, false>(P, grid, st);
   }
 }
 

@@ -30,6 +30,7 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(GatherParams P) {
         P.idx_pad[(size_t)g * P.idx_pad_stride + c] = (c < cnt) ? P.idx[(size_t)g * P.idx_stride + c] : 0x7FFFFFFF;
     }
   }
+  if (P.out_t == nullptr && P.out_rows == nullptr) return;   // only the padded index list was wanted
   if (c0 >= ((cnt + 63) & ~63)) return;   // nothing reads beyond the last partial tile
   const uint16_t* src = P.src + (size_t)((P.head0 + g) / P.group) * P.S * kHeadDim;
 #pragma unroll

@@ -117,8 +117,10 @@ struct SparseWs {
   size_t vt, kc, vct, cidx, cbits, obits, dlist, dcnt, total;
   int cb_words, rb_words, dlist_stride, off_max;
 };
-// n_heads: the (batch * query) heads whose metadata and gathered K/V are resident at once
-SparseWs sparse_ws(const Dims& d, int n_heads) {
+// n_heads: the (batch * query) heads whose metadata and gathered K/V are resident at once;
+// gathered: room for the per-head copies of the kept columns' K and V^T (the strip path;
+// the block path reads its key blocks in place)
+SparseWs sparse_ws(const Dims& d, int n_heads, bool gathered = true) {
   SparseWs w;
   w.cb_words = d.S_pad / 32 + 2;
   w.rb_words = d.S_pad / 32 + 24;
@@ -126,8 +128,8 @@ SparseWs sparse_ws(const Dims& d, int n_heads) {
   w.off_max = d.S_pad - 1;
   size_t at = 0;
   w.vt = at;    at += align_up((size_t)d.n_bkv * sa::kHeadDim * d.S_pad * 2);
-  w.kc = at;    at += align_up((size_t)n_heads * d.S_pad * sa::kHeadDim * 2);
-  w.vct = at;   at += align_up((size_t)n_heads * sa::kHeadDim * d.S_pad * 2);
+  w.kc = at;    at += gathered ? align_up((size_t)n_heads * d.S_pad * sa::kHeadDim * 2) : 0;
+  w.vct = at;   at += gathered ? align_up((size_t)n_heads * sa::kHeadDim * d.S_pad * 2) : 0;
   w.cidx = at;  at += align_up((size_t)n_heads * d.S_pad * 4);
   w.cbits = at; at += align_up((size_t)n_heads * w.cb_words * 4);
   w.obits = at; at += align_up((size_t)n_heads * w.rb_words * 4);
@@ -140,7 +142,7 @@ SparseWs sparse_ws(const Dims& d, int n_heads) {
 struct BlockWs { SparseWs sp; size_t tok_idx, tok_cnt, dbits, total; int nb, db_words; };
 BlockWs block_ws(const Dims& d, int blk, int n_heads) {
   BlockWs w;
-  w.sp = sparse_ws(d, n_heads);
+  w.sp = sparse_ws(d, n_heads, false);
   w.nb = (d.S + blk - 1) / blk;
   w.db_words = (w.nb + 1) / 32 + 1;
   size_t at = w.sp.total;
@@ -496,12 +498,15 @@ sa_status prepare_heads(const Dims& d, const BlockWs& bw, int granularity, int h
   if (s != SA_OK) return s;
   *cnt_used = col_cnt;
 
-  // column side: compact K rows and V^T columns of the kept keys, per query head
+  // column side: compact K rows and V^T columns of the kept keys, per query head.  Key
+  // blocks are runs of consecutive keys and are read in place: only the padded index
+  // list (the tiles' key indices) is written then.
   sa::GatherParams G;
   memset(&G, 0, sizeof(G));
   G.idx = col_idx; G.cnt = col_cnt; G.idx_stride = d.S;
   G.idx_pad = reinterpret_cast<int32_t*>(ws + w.cidx); G.idx_pad_stride = d.S_pad;
   G.n_out = nh; G.group = d.group; G.head0 = h0; G.S = d.S; G.C_pad = d.S_pad;
+  if (blocks) return dev(sa::launch_gather_transpose(G, st));
   G.src = static_cast<const uint16_t*>(v);
   G.out_t = reinterpret_cast<uint16_t*>(ws + w.vct);
   s = dev(sa::launch_gather_transpose(G, st));
@@ -515,7 +520,7 @@ sa_status prepare_heads(const Dims& d, const BlockWs& bw, int granularity, int h
 }
 
 // the strip-masked kernel on query tiles [qtile0, qtile0 + n_qtiles) of the heads [h0, h0 + nh)
-sa_status launch_attend(const Dims& d, const SparseWs& w, int h0, int nh, int qtile0, int n_qtiles,
+sa_status launch_attend(const Dims& d, const SparseWs& w, bool blocks, int h0, int nh, int qtile0, int n_qtiles,
                         int row_lo, int row_hi, const void* q, const void* k, const int32_t* col_cnt,
                         void* out, int out_dtype, float* out_lse, uint64_t* tiles, char* ws, hipStream_t st) {
   sa::FlashParams P = base_flash(d, q, k);
@@ -532,8 +537,9 @@ sa_status launch_attend(const Dims& d, const SparseWs& w, int h0, int nh, int qt
   P.row_lo = row_lo;
   P.n_qrows = row_hi;
   P.vt = reinterpret_cast<const uint16_t*>(ws + w.vt);
-  P.kc = reinterpret_cast<const uint16_t*>(ws + w.kc);
-  P.vct = reinterpret_cast<const uint16_t*>(ws + w.vct);
+  P.cols_in_place = blocks ? 1 : 0;
+  P.kc = blocks ? nullptr : reinterpret_cast<const uint16_t*>(ws + w.kc);
+  P.vct = blocks ? nullptr : reinterpret_cast<const uint16_t*>(ws + w.vct);
   P.col_idx_pad = reinterpret_cast<const int32_t*>(ws + w.cidx);
   P.col_cnt = col_cnt;
   P.col_bits = reinterpret_cast<const uint32_t*>(ws + w.cbits);
@@ -576,7 +582,8 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity, cons
     return SA_ERR_INVALID_ARG;
   if (local_window < 1) return SA_ERR_INVALID_ARG;
   if (out_dtype != SA_OUT_BF16 && out_dtype != SA_OUT_F32) return SA_ERR_INVALID_ARG;
-  const BlockWs bw = block_ws(d, blocks ? granularity : 64, heads_per_pass);
+  BlockWs bw = block_ws(d, blocks ? granularity : 64, heads_per_pass);
+  if (!blocks) bw.sp = sparse_ws(d, heads_per_pass, true);
   s = check_ws(workspace, workspace_bytes, blocks ? bw.total : bw.sp.total);
   if (s != SA_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -610,7 +617,7 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity, cons
       for (int g = 0; g < segs; ++g) {
         const int a0 = qtile0 + (int)((long long)(qtile1 - qtile0) * g / segs);
         const int a1 = qtile0 + (int)((long long)(qtile1 - qtile0) * (g + 1) / segs);
-        s = launch_attend(d, bw.sp, h0, nh, a0, a1 - a0, row_lo, row_hi, q, k, cnt_used, out, out_dtype, out_lse,
+        s = launch_attend(d, bw.sp, blocks, h0, nh, a0, a1 - a0, row_lo, row_hi, q, k, cnt_used, out, out_dtype, out_lse,
                           tiles, ws, st);
         if (s != SA_OK) return s;
       }

@@ -23,6 +23,8 @@ struct FlashParams {
   int n_qtiles;             // 256-row query tiles to process
   int qtile0;               // strip-masked mode: the first of them (a segment of the queries)
   int q_row0, n_qrows;      // first query row and number of rows (sampled rows in mode 1)
+  int cols_in_place;        // strip-masked mode, block lists: column tiles are read from k / vt themselves
+                            // (kc, vct unused); col_idx_pad then holds runs of 64 consecutive keys per tile
   int row_lo;               // strip-masked mode: rows below it are neither computed for nor written
                             // (rows [row_lo, n_qrows) of the launch's query tiles are; q_row0 = 0 there)
   int k_splits;             // mode 1: the keys of a query tile are cut into this many workgroups (>= 1);
@@ -48,7 +50,7 @@ hipError_t launch_lse_combine(const float* part, float* out, size_t n, int k, hi
 // out[g][d][c] = src[kv(g)][idx ? idx[g][c] : c][d] for c < cnt (zero beyond, up to C_pad);
 // optionally also rows_out[g][c][:] = src[kv(g)][idx[g][c]][:]
 struct GatherParams {
-  const uint16_t* src;      // [n_src, S, 128]
+  const uint16_t* src;      // [n_src, S, 128]; may be null when only idx_pad is wanted
   const int32_t* idx;       // nullable [n_out, idx_stride]
   const int32_t* cnt;       // nullable [n_out]; null -> S
   uint16_t* out_t;          // [n_out, 128, C_pad]
