@@ -253,6 +253,9 @@ def main() -> int:
     ap.add_argument("--no-alpha-grid", action="store_true",
                     help="skip the grid of separate column / slash thresholds on the three head patterns")
     ap.add_argument("--no-peaks", action="store_true", help="skip the MFMA / copy peak probes")
+    ap.add_argument("--heads-per-pass", type=int, default=0,
+                    help="bound the workspace (long sequences): stage 1 and the attention take this many heads at a "
+                         "time (sa_sparse_attn_partitioned); 0 = all heads at once")
     ap.add_argument("--sampling-study", action="store_true",
                     help="compare masks chosen from sampled scores with masks chosen from the scores of ALL rows "
                          "at equal strip budgets (recall of the dense softmax), then exit")
@@ -286,7 +289,9 @@ def main() -> int:
     log(f"inputs generated on the host in {time.perf_counter() - t0:.1f} s")
     q, k, v = to_device(x["q"]), to_device(x["k"]), to_device(x["v"])
     shape = sa.Shape(1, Hq, Hkv, S)
-    plan = sa.SampleAttentionPlan(shape, n_s)
+    plan = sa.SampleAttentionPlan(shape, n_s, heads_per_pass=args.heads_per_pass or None)
+    log(f"plan workspace {plan.ws.numel() / 1e9:.2f} GB"
+        + (f" ({args.heads_per_pass} heads per pass)" if args.heads_per_pass else ""))
     torch.cuda.synchronize()
 
     if args.sampling_study:
@@ -320,7 +325,17 @@ def main() -> int:
     ms_median = float(np.median(step_ms))
     stage = {name: sa.sa_profile_read(name) for name in
              ("row_lse", "score_accum", "score_final", "select", "transpose_v", "mask_prep", "sparse_flash")}
-    stage_ms = {n: (float(np.mean(vv)) if vv else None) for n, vv in stage.items()}
+    # a kernel may run several times per step (one launch per pass over a group of heads); the
+    # library keeps the last 64 launches of each kernel, i.e. a whole number m of the last steps
+    def per_step(vv):
+        if not vv:
+            return None
+        if len(vv) % args.steps == 0 and len(vv) < 64:
+            return float(np.sum(vv)) / args.steps
+        per = max(1, -(-Hq // (args.heads_per_pass or Hq)))          # launches per step
+        m = max(1, len(vv) // per)
+        return float(np.sum(vv[-m * per:])) / m
+    stage_ms = {n: per_step(vv) for n, vv in stage.items()}
     log(f"ms/step: median of events {ms_median:.3f}, wall-clock mean {ms_per_step:.3f}; stages {json.dumps(stage_ms)}")
 
     tiles = plan.tiles.cpu().numpy().astype(np.int64)
@@ -590,6 +605,8 @@ def main() -> int:
         "idle_slot_share": 1.0 - float(tiles.sum()) / slots,
         "kept_pair_fraction": kept_pairs / (Hq * S * (S + 1) / 2.0),
         "workspace_bytes": ws_bytes,
+        "plan_workspace_bytes": int(plan.ws.numel()),
+        "heads_per_pass": args.heads_per_pass or Hq,
         "measured_peaks": peaks,
         "computed_tile_fraction": float(tiles.sum()) / dense_tiles,
         "mask_density_head0": density0,

@@ -500,15 +500,29 @@ class SampleAttentionPlan:
     and nothing else (no allocation, no host synchronisation)."""
 
     def __init__(self, shape: Shape, n_sample_rows: int, device="cuda", out_dtype: int = SA_OUT_BF16,
-                 granularity: int = 1, n_chunks: int = 1, with_lse: bool = False):
+                 granularity: int = 1, n_chunks: int = 1, with_lse: bool = False,
+                 heads_per_pass: Optional[int] = None, n_query_segments: int = 1):
+        """``heads_per_pass``: bound the workspace (long sequences): the attention call is
+        sa_sparse_attn_partitioned with that many heads per pass, and stage 1 gets room for
+        as many heads per pass (per-key strips, one chunk only)."""
         lib = load_library()
         self.lib, self.shape, self.n_s, self.out_dtype = lib, shape, n_sample_rows, out_dtype
         self.granularity, self.n_chunks = granularity, n_chunks
         self.cs = shape.c()
         self.sm = _CSampling(n_sample_rows, n_chunks, granularity)
-        ops = (SA_OP_SAMPLE_SCORES, SA_OP_SPARSE_ATTN if granularity == 1 else SA_OP_BLOCK_SPARSE_ATTN,
-               SA_OP_DENSE_ATTN)
-        sizes = [int(lib.sa_workspace_bytes(op, ctypes.byref(self.cs), ctypes.byref(self.sm))) for op in ops]
+        self.part = None
+        if heads_per_pass is not None:
+            if granularity != 1 or n_chunks != 1:
+                raise ValueError("the head partition is offered for per-key strips with one chunk")
+            self.part = _CPartition(heads_per_pass, n_query_segments)
+            one_head = int(lib.sa_workspace_bytes(SA_OP_SAMPLE_SCORES_MIN, ctypes.byref(self.cs), ctypes.byref(self.sm)))
+            sizes = [one_head * heads_per_pass + 4096,
+                     int(lib.sa_partitioned_workspace_bytes(ctypes.byref(self.cs), ctypes.byref(self.part))),
+                     int(lib.sa_workspace_bytes(SA_OP_DENSE_ATTN, ctypes.byref(self.cs), ctypes.byref(self.sm)))]
+        else:
+            ops = (SA_OP_SAMPLE_SCORES, SA_OP_SPARSE_ATTN if granularity == 1 else SA_OP_BLOCK_SPARSE_ATTN,
+                   SA_OP_DENSE_ATTN)
+            sizes = [int(lib.sa_workspace_bytes(op, ctypes.byref(self.cs), ctypes.byref(self.sm))) for op in ops]
         if min(sizes) == 0:
             raise ValueError("invalid shape or sampling for this library")
         need = max(sizes)
@@ -555,6 +569,14 @@ class SampleAttentionPlan:
                                            _ptr(self.slash_cnt), None, 0, _stream()), "sa_select_strips")
 
     def attend(self, q, k, v, window):
+        if self.part is not None:
+            self._ok(self.lib.sa_sparse_attn_partitioned(ctypes.byref(self.cs), ctypes.byref(self.part), _ptr(q),
+                                                         _ptr(k), _ptr(v), _ptr(self.col_idx), _ptr(self.col_cnt),
+                                                         _ptr(self.slash_idx), _ptr(self.slash_cnt), int(window),
+                                                         _ptr(self.out), self.out_dtype, _ptr(self.lse),
+                                                         _ptr(self.tiles), _ptr(self.ws), self.ws.numel(), _stream()),
+                     "sa_sparse_attn_partitioned")
+            return
         if self.n_chunks != 1:
             self._ok(self.lib.sa_sparse_attn_chunked(ctypes.byref(self.cs), ctypes.byref(self.sm), _ptr(q), _ptr(k),
                                                      _ptr(v), _ptr(self.col_idx), _ptr(self.col_cnt),
