@@ -59,6 +59,14 @@ constexpr int LDS_B_LSE = OFF_DUMP_LSE + 8 * 1024;  // 73728 bytes
 constexpr float kSumBound = 256.0f;    // a tile's exponentials may sum to 2^8 per lane before the reference maximum moves
 
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
+// What a stretch of the tile loop knows at compile time about the tiles it touches
+// (the tile of an iteration, the one before and the four ahead): nothing, all of them
+// gathered-column tiles, or none of them.  The strip-masked kernel runs its loop in
+// three stretches, so that the long ones carry no per-tile choice between the two
+// kinds of addressing, aux words and activity tests.
+using AnyTiles = std::integral_constant<int, 0>;
+using ColTiles = std::integral_constant<int, 1>;
+using RngTiles = std::integral_constant<int, 2>;
 
 // a wave-uniform 64-bit value / pointer, forced into scalar registers (the inline
 // assembly below takes its base address in a scalar register pair; left alone, the
@@ -226,21 +234,26 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // values come from a list in global memory; they are fetched (fetch_d) four tiles
   // ahead of their first use and handed on in scalar registers, so that no phase
   // waits on a scalar load.
-  auto fetch_d = [&](int t) -> int {
+  // kind of tile t (wave-uniform; no memory access); `real`: t lies inside the schedule
+  auto is_col = [&](auto kc, int t) __attribute__((always_inline)) -> bool {
+    constexpr int KC = decltype(kc)::value;
+    return MODE == 2 && (KC == 1 || (KC == 0 && t < n_col_tiles));
+  };
+  auto is_real = [&](auto kc, int t) __attribute__((always_inline)) -> bool { return decltype(kc)::value == 1 || t < n_tiles; };
+  auto fetch_d = [&](auto kc, int t) __attribute__((always_inline)) -> int {
     // read through the constant address space: the list is not written while the kernel
     // runs, and only so does the load stay a scalar one (tracked apart from the vector
     // loads in flight) behind the barriers and inline assembly of the loop
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
-    if (IN_PLACE && t < n_col_tiles)
+    if (IN_PLACE && is_col(kc, t))
       return ((const_i32_ptr)(uintptr_t)cidx)[BK * t];                       // first key of the tile's block
-    if (MODE == 2 && t >= n_col_tiles && t < n_tiles)
+    if (MODE == 2 && !is_col(kc, t) && t < n_tiles)
       return ((const_i32_ptr)(uintptr_t)dl)[n_rng - 1 - (t - n_col_tiles)];   // far to near
     return 0;
   };
-  // kind and first key of tile t (wave-uniform; no memory access)
-  auto is_col = [&](int t) -> bool { return MODE == 2 && t < n_col_tiles; };
-  auto first_key = [&](int t, int d) -> int {          // contiguous tiles only; d = list entry
-    if (IN_PLACE && t < n_col_tiles) return d;         // the entry of an in-place column tile is its first key
+  // first key of tile t
+  auto first_key = [&](auto kc, int t, int d) __attribute__((always_inline)) -> int {  // contiguous tiles only; d = list entry
+    if (IN_PLACE && is_col(kc, t)) return d;         // the entry of an in-place column tile is its first key
     return (MODE == 2) ? (a64 + 3 - (d & kDiagMask)) * BK : (t + (MODE == 1 ? t_base : 0)) * BK;
   };
   // array bases as scalars, once
@@ -295,21 +308,21 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   uint32_t ld_vdst = 0, ld_kdst = 0, ld_vstep = 0, ld_kstep = 0, ld_klim = 0;   // step: LDS distance of run w + 8
   // A tile past the end of the schedule is replaced by a stand-in: the first tile of
   // K / V^T, always readable, loaded into the wave's dump kilobyte.
-  auto load_v_begin = [&](int t, int d) {
+  auto load_v_begin = [&](auto kc, int t, int d) __attribute__((always_inline)) {
     if (!WITH_V) return;
-    const bool real = t < n_tiles, col = !IN_PLACE && real && is_col(t);   // col: from the gathered copy
-    const uint32_t off = !real ? 0u : (col ? (uint32_t)t : (uint32_t)first_key(t, d)) * 2u;   // bytes into a V^T row; t * 64 keys for a gathered tile
+    const bool real = is_real(kc, t), col = !IN_PLACE && real && is_col(kc, t);   // col: from the gathered copy
+    const uint32_t off = !real ? 0u : (col ? (uint32_t)t : (uint32_t)first_key(kc, t, d)) * 2u;   // bytes into a V^T row; t * 64 keys for a gathered tile
     ld_vbase = col ? s_vct + (uint64_t)((uint32_t)t * (BK * 2u)) : s_vtbase + off;
     ld_vbase1 = ld_vbase + 128ull * (uint32_t)P.S_pad;            // run w + 8: 64 rows of V^T further on
     ld_vdst = smem_lds + 1024 * wave + (real ? OFF_V + (t & (NSTAGE - 1)) * VTILE_B : kOffDump);
     ld_vstep = real ? 8192 : 0;                    // a stand-in tile writes both runs to the same dump kilobyte
   };
-  auto load_k_begin = [&](int t, int d) {
-    const bool real = t < n_tiles, col = !IN_PLACE && real && is_col(t);
+  auto load_k_begin = [&](auto kc, int t, int d) __attribute__((always_inline)) {
+    const bool real = is_real(kc, t), col = !IN_PLACE && real && is_col(kc, t);
     const int kmax = col ? P.S_pad - 1 : S - 1;    // last row of the array that may be read
     // a range tile may start past the last key (all of it masked): the base row is
     // clamped, and so is each lane's byte offset, to the last row that exists
-    const int row0 = min(!real ? 0 : (col ? t * BK : first_key(t, d)), kmax);
+    const int row0 = min(!real ? 0 : (col ? t * BK : first_key(kc, t, d)), kmax);
     ld_kbase = (col ? s_kc : s_kbase) + ((uint64_t)(uint32_t)row0 << 8);
     ld_klim = (uint32_t)(kmax - row0) * KROW_B + (koff0 & (KROW_B - 1));
     ld_kdst = smem_lds + 1024 * wave + (real ? OFF_K + (t & (NSTAGE - 1)) * KTILE_B : kOffDump);
@@ -326,14 +339,14 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // range tile 16 words of the offset bitmap (covering every offset of the 256 x 64
   // tile) followed by the 2 words of the column bitmap.  One load, by wave t % 8.
   const uint32_t aux_lane = lane < 16 ? 4u * lane : 4u * (lane & 1);
-  auto dma_aux = [&](int t, int d) {
+  auto dma_aux = [&](auto kc, int t, int d) __attribute__((always_inline)) {
     if (MODE != 2 || wave != (t & 7)) return;
-    const bool real = t < n_tiles;
+    const bool real = is_real(kc, t);
     const uint32_t dst = smem_lds + (real ? OFF_A + (t & (NAUX - 1)) * AUX_B : kOffDump);
-    if (real && is_col(t)) {
+    if (real && is_col(kc, t)) {
       dma4(s_cidx + (uint64_t)((uint32_t)t * (BK * 4u)), 4u * lane, dst);
     } else {
-      const int j0 = real ? first_key(t, d) : 0;
+      const int j0 = real ? first_key(kc, t, d) : 0;
       const int wb = (P.off_max - (i0 - j0 + BQ - 1)) >> 5;          // first offset-bitmap word needed
       // lanes 0..15: offset words wb ..; lanes 16..63: the two column words, alternating.
       // The column bitmaps lie below the offset bitmaps in the workspace (and within
@@ -354,20 +367,20 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   //    tile must start before the sequence end.
   // The aux words are read early (act_words) and looked at later (tile_active), so
   // that the wait for them hides behind MFMAs.
-  auto act_words = [&](int t, uint32_t& w0, uint32_t& w1) {
+  auto act_words = [&](auto kc, int t, uint32_t& w0, uint32_t& w1) __attribute__((always_inline)) {
     if (MODE != 2) return;
     const uint32_t* ax = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
-    if (t < n_col_tiles) {
+    if (is_col(kc, t)) {
       w0 = ax[0];
     } else {
       w0 = ax[16];
       w1 = ax[17];
     }
   };
-  auto tile_active = [&](int t, int d, uint32_t w0, uint32_t w1) -> bool {
+  auto tile_active = [&](auto kc, int t, int d, uint32_t w0, uint32_t w1) __attribute__((always_inline)) -> bool {
     bool act;
-    const int j0 = first_key(t, d);
-    if (is_col(t)) {
+    const int j0 = first_key(kc, t, d);
+    if (is_col(kc, t)) {
       act = (int)w0 <= iw0 + 31;
     } else if (MODE == 2) {
       act = (((uint32_t)d >> (24 + wave)) & 1u) && ((w0 & w1) != 0xFFFFFFFFu) && (j0 < S);
@@ -462,9 +475,9 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   };
 
   // ---- the softmax phase: mask, online softmax (one query per lane), bf16 --------
-  auto step_softmax = [&](int t, int d) {
-    const int j0 = first_key(t, d);
-    const int kind = is_col(t) ? TK_COLIDX : (MODE == 2) ? TK_RANGE : (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
+  auto step_softmax = [&](auto kc, int t, int d) __attribute__((always_inline)) {
+    const int j0 = first_key(kc, t, d);
+    const int kind = is_col(kc, t) ? TK_COLIDX : (MODE == 2) ? TK_RANGE : (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
     const int buf = t & (NSTAGE - 1);
     // Mask: one 32-bit pattern per lane and 32-key half, bit b <-> key
     // j0 + 32 sb + 8 hf + b of the lane's 16 (b = 0..7, 16..23), set = keep.  The
@@ -607,7 +620,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   unsigned long long tiles_done = 0;
   bool act_t = false;                        // this wave has work on the tile whose softmax comes next
   bool pre_done = false, pre_act = false;    // the next tile was already looked at (and the ring warmed for it)
-  int dq0 = fetch_d(0), dq1 = fetch_d(1), dq2 = fetch_d(2), dq3 = fetch_d(3);   // tile diagonals of tiles u .. u+3
+  int dq0 = fetch_d(AnyTiles{}, 0), dq1 = fetch_d(AnyTiles{}, 1), dq2 = fetch_d(AnyTiles{}, 2), dq3 = fetch_d(AnyTiles{}, 3);   // tile diagonals of tiles u .. u+3
   // The scores, the probabilities and the operand ring are written on some paths only
   // (a wave may have no work on a tile).  An empty asm that "defines" them where their
   // old contents are dead tells the compiler so; without it every path that skips a
@@ -620,39 +633,39 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     for (int i = 0; i < 8; ++i) asm volatile("" : "=v"(pk[0][i]), "=v"(pk[1][i]));
   };
   auto forget_scores = [&]() { asm volatile("" : "=v"(s[0]), "=v"(s[1])); };
-  auto softmax_phase = [&](int u, int d_u, int d_next, int it) {   // tile diagonals of tiles u and u + 1; iteration
+  auto softmax_phase = [&](auto kc, int u, int d_u, int d_next, int it) __attribute__((always_inline)) {   // tile diagonals of tiles u and u + 1; iteration
     forget_ring_and_p();                     // consumed by the MFMA phase before
     if (kLoadsInSoftmax) {
       // the loads of iteration `it`: aux(it + 3), V(it + 2), K(it + 3)
-      dma_aux(it + 3, dq3);
-      load_v_begin(it + 2, dq2);
-      load_k_begin(it + 3, dq3);
+      dma_aux(kc, it + 3, dq3);
+      load_v_begin(kc, it + 2, dq2);
+      load_k_begin(kc, it + 3, dq3);
       if (!act_t) { load_v_one(0); load_v_one(1); load_k_one(0); load_k_one(1); }
     }
-    if (act_t) step_softmax(u, d_u);
+    if (act_t) step_softmax(kc, u, d_u);
     // A wave with nothing to do here looks at the next tile now, so that its next MFMA
     // phase knows at once whether it has work.
-    if (!act_t && u + 1 < n_tiles) {
+    if (!act_t && is_real(kc, u + 1)) {
       uint32_t w0 = 0, w1 = 0;
-      act_words(u + 1, w0, w1);
-      pre_act = tile_active(u + 1, d_next, w0, w1);
+      act_words(kc, u + 1, w0, w1);
+      pre_act = tile_active(kc, u + 1, d_next, w0, w1);
       pre_done = true;
     }
   };
-  auto mfma_phase = [&](int u) {
+  auto mfma_phase = [&](auto kc, int u) __attribute__((always_inline)) {
     forget_scores();                         // consumed by the softmax phase before
-    const bool have = u < n_tiles;
-    auto setup_a = [&]() { dma_aux(u + 3, dq3); };
-    auto setup_v = [&]() { load_v_begin(u + 2, dq2); };
-    auto setup_k = [&]() { load_k_begin(u + 3, dq3); };
+    const bool have = is_real(kc, u);
+    auto setup_a = [&]() { dma_aux(kc, u + 3, dq3); };
+    auto setup_v = [&]() { load_v_begin(kc, u + 2, dq2); };
+    auto setup_k = [&]() { load_k_begin(kc, u + 3, dq3); };
     auto ahead_setup = [&]() { setup_a(); setup_v(); setup_k(); };
     __builtin_amdgcn_s_setprio(1);
     const bool pv = WITH_V && act_t;
     bool act_n = false;
     if (pv) {
       uint32_t aw0 = 0, aw1 = 0;
-      auto look = [&]() { if (have) act_words(u, aw0, aw1); };
-      auto decide = [&]() { act_n = have && tile_active(u, dq0, aw0, aw1); };
+      auto look = [&]() { if (have) act_words(kc, u, aw0, aw1); };
+      auto decide = [&]() { act_n = have && tile_active(kc, u, dq0, aw0, aw1); };
       mm_pv((u - 1) & (NSTAGE - 1), u & (NSTAGE - 1), setup_a, setup_v, setup_k, look, decide);
     } else {
       if (!kLoadsInSoftmax) ahead_setup();
@@ -664,8 +677,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
           act_n = pre_act;
         } else if (have) {
           uint32_t aw0 = 0, aw1 = 0;
-          act_words(u, aw0, aw1);
-          act_n = tile_active(u, dq0, aw0, aw1);
+          act_words(kc, u, aw0, aw1);
+          act_n = tile_active(kc, u, dq0, aw0, aw1);
         }
         if (act_n) warm_k(u & (NSTAGE - 1));
       } else if (pre_done) {
@@ -673,8 +686,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
         if (act_n) warm_k(u & (NSTAGE - 1));
       } else if (have) {
         uint32_t aw0 = 0, aw1 = 0;
-        act_words(u, aw0, aw1);
-        act_n = tile_active(u, dq0, aw0, aw1);
+        act_words(kc, u, aw0, aw1);
+        act_n = tile_active(kc, u, dq0, aw0, aw1);
         if (act_n) warm_k(u & (NSTAGE - 1));
       }
     }
@@ -698,12 +711,15 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
 #undef SA_PIN
 
   // prologue: K(0..2), V(0..1) and the aux words of tiles 0..2
-  dma_aux(0, dq0); dma_aux(1, dq1); dma_aux(2, dq2);
-  load_k_begin(0, dq0); load_k_one(0); load_k_one(1);
-  load_k_begin(1, dq1); load_k_one(0); load_k_one(1);
-  load_k_begin(2, dq2); load_k_one(0); load_k_one(1);
-  load_v_begin(0, dq0); load_v_one(0); load_v_one(1);
-  load_v_begin(1, dq1); load_v_one(0); load_v_one(1);
+  {
+    const AnyTiles any{};
+    dma_aux(any, 0, dq0); dma_aux(any, 1, dq1); dma_aux(any, 2, dq2);
+    load_k_begin(any, 0, dq0); load_k_one(0); load_k_one(1);
+    load_k_begin(any, 1, dq1); load_k_one(0); load_k_one(1);
+    load_k_begin(any, 2, dq2); load_k_one(0); load_k_one(1);
+    load_v_begin(any, 0, dq0); load_v_one(0); load_v_one(1);
+    load_v_begin(any, 1, dq1); load_v_one(0); load_v_one(1);
+  }
   // vmcnt(0), as the builtin: the compiler then also knows that the Q loads above have
   // landed and places no waits of its own for them inside the loop, where they would
   // wait for the loads in flight there as well
@@ -717,27 +733,40 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // wave of every SIMD on the matrix pipe while the other is on the vector pipe.
   // (The loop is written out once per group: one loop that picks the phase at run
   // time keeps the registers of both phases alive everywhere and spills.)
+  // Iteration n touches tiles n - 1 .. n + 4.  In the strip-masked kernel the iterations
+  // n + 4 < n_col_tiles see gathered tiles only, the iterations n > n_col_tiles range
+  // tiles only; the few in between take the general form.
+  const int n_gen0 = (MODE == 2) ? max(n_col_tiles - 4, 0) : 0;            // first iteration of the general form
+  const int n_gen1 = (MODE == 2) ? min(n_col_tiles, n_tiles) : n_tiles;    // its last
   if (grp == 0) {
-    for (int n = 0; n <= n_tiles; ++n) {
+    auto iteration = [&](auto kc, int n) __attribute__((always_inline)) {
       // the scalar load is issued here and collected by the barrier's lgkmcnt(0): waited
       // for anywhere else, it would drain the LDS reads in flight as well
-      const int dq4 = fetch_d(n + 4);
-      mfma_phase(n);                         // n = 0: K Q^T(0) only; n = n_tiles: the last P V
-      softmax_phase(n, dq0, dq1, n);
+      const int dq4 = fetch_d(kc, n + 4);
+      mfma_phase(kc, n);                     // n = 0: K Q^T(0) only; n = n_tiles: the last P V
+      softmax_phase(kc, n, dq0, dq1, n);
       end_of_iteration_wait();
       wg_barrier();
       dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
-    }
+    };
+    int n = 0;
+    if (MODE == 2) for (; n < n_gen0; ++n) iteration(ColTiles{}, n);
+    for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
+    if (MODE == 2) for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
   } else {
     int dprev = 0;                           // tile diagonal of tile n - 1
-    for (int n = 0; n <= n_tiles; ++n) {
-      const int dq4 = fetch_d(n + 4);
-      softmax_phase(n - 1, dprev, dq0, n);
-      mfma_phase(n);
+    auto iteration = [&](auto kc, int n) __attribute__((always_inline)) {
+      const int dq4 = fetch_d(kc, n + 4);
+      softmax_phase(kc, n - 1, dprev, dq0, n);
+      mfma_phase(kc, n);
       end_of_iteration_wait();
       wg_barrier();
       dprev = dq0; dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
-    }
+    };
+    int n = 0;
+    if (MODE == 2) for (; n < n_gen0; ++n) iteration(ColTiles{}, n);
+    for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
+    if (MODE == 2) for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
   }
   vm_wait<0>();                              // nothing may still be writing LDS when the workgroup ends
 
