@@ -60,13 +60,21 @@ constexpr float kSumBound = 256.0f;    // a tile's exponentials may sum to 2^8 p
 
 enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 };
 // What a stretch of the tile loop knows at compile time about the tiles it touches
-// (the tile of an iteration, the one before and the four ahead): nothing, all of them
-// gathered-column tiles, or none of them.  The strip-masked kernel runs its loop in
-// three stretches, so that the long ones carry no per-tile choice between the two
-// kinds of addressing, aux words and activity tests.
-using AnyTiles = std::integral_constant<int, 0>;
-using ColTiles = std::integral_constant<int, 1>;
-using RngTiles = std::integral_constant<int, 2>;
+// (the tile of an iteration, the one before and the four ahead).  KIND: nothing (0),
+// all of them gathered-column tiles (1), or none of them (2); REAL: all of them lie
+// inside the schedule.  The loop runs in stretches, so that the long ones carry no
+// per-tile choice between the two kinds of addressing, aux words and activity tests,
+// and no stand-ins for tiles past the end.
+template <int KIND_, bool REAL_>
+struct Stretch {
+  static constexpr int KIND = KIND_;
+  static constexpr bool REAL = REAL_;
+};
+using AnyTiles = Stretch<0, false>;
+using AnyRealTiles = Stretch<0, true>;
+using ColTiles = Stretch<1, true>;
+using RngTiles = Stretch<2, false>;
+using RngRealTiles = Stretch<2, true>;
 
 // a wave-uniform 64-bit value / pointer, forced into scalar registers (the inline
 // assembly below takes its base address in a scalar register pair; left alone, the
@@ -236,10 +244,10 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // waits on a scalar load.
   // kind of tile t (wave-uniform; no memory access); `real`: t lies inside the schedule
   auto is_col = [&](auto kc, int t) __attribute__((always_inline)) -> bool {
-    constexpr int KC = decltype(kc)::value;
-    return MODE == 2 && (KC == 1 || (KC == 0 && t < n_col_tiles));
+    constexpr int KIND = decltype(kc)::KIND;
+    return MODE == 2 && (KIND == 1 || (KIND == 0 && t < n_col_tiles));
   };
-  auto is_real = [&](auto kc, int t) __attribute__((always_inline)) -> bool { return decltype(kc)::value == 1 || t < n_tiles; };
+  auto is_real = [&](auto kc, int t) __attribute__((always_inline)) -> bool { return decltype(kc)::REAL || t < n_tiles; };
   auto fetch_d = [&](auto kc, int t) __attribute__((always_inline)) -> int {
     // read through the constant address space: the list is not written while the kernel
     // runs, and only so does the load stay a scalar one (tracked apart from the vector
@@ -247,7 +255,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
     if (IN_PLACE && is_col(kc, t))
       return ((const_i32_ptr)(uintptr_t)cidx)[BK * t];                       // first key of the tile's block
-    if (MODE == 2 && !is_col(kc, t) && t < n_tiles)
+    if (MODE == 2 && !is_col(kc, t) && is_real(kc, t))
       return ((const_i32_ptr)(uintptr_t)dl)[n_rng - 1 - (t - n_col_tiles)];   // far to near
     return 0;
   };
@@ -735,9 +743,11 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // time keeps the registers of both phases alive everywhere and spills.)
   // Iteration n touches tiles n - 1 .. n + 4.  In the strip-masked kernel the iterations
   // n + 4 < n_col_tiles see gathered tiles only, the iterations n > n_col_tiles range
-  // tiles only; the few in between take the general form.
+  // tiles only; the few in between take the general form.  The iterations n + 4 <
+  // n_tiles see no tile past the end of the schedule.
   const int n_gen0 = (MODE == 2) ? max(n_col_tiles - 4, 0) : 0;            // first iteration of the general form
-  const int n_gen1 = (MODE == 2) ? min(n_col_tiles, n_tiles) : n_tiles;    // its last
+  const int n_gen1 = (MODE == 2) ? min(n_col_tiles, n_tiles) : -1;         // its last
+  const int n_real = n_tiles - 4;                                          // first iteration that may see a tile past the end
   if (grp == 0) {
     auto iteration = [&](auto kc, int n) __attribute__((always_inline)) {
       // the scalar load is issued here and collected by the barrier's lgkmcnt(0): waited
@@ -750,9 +760,15 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
     };
     int n = 0;
-    if (MODE == 2) for (; n < n_gen0; ++n) iteration(ColTiles{}, n);
-    for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
-    if (MODE == 2) for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
+    if (MODE == 2) {
+      for (; n < n_gen0; ++n) iteration(ColTiles{}, n);
+      for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
+      for (; n < n_real; ++n) iteration(RngRealTiles{}, n);
+      for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
+    } else {
+      for (; n < n_real; ++n) iteration(AnyRealTiles{}, n);
+      for (; n <= n_tiles; ++n) iteration(AnyTiles{}, n);
+    }
   } else {
     int dprev = 0;                           // tile diagonal of tile n - 1
     auto iteration = [&](auto kc, int n) __attribute__((always_inline)) {
@@ -764,9 +780,15 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       dprev = dq0; dq0 = dq1; dq1 = dq2; dq2 = dq3; dq3 = dq4;
     };
     int n = 0;
-    if (MODE == 2) for (; n < n_gen0; ++n) iteration(ColTiles{}, n);
-    for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
-    if (MODE == 2) for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
+    if (MODE == 2) {
+      for (; n < n_gen0; ++n) iteration(ColTiles{}, n);
+      for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
+      for (; n < n_real; ++n) iteration(RngRealTiles{}, n);
+      for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
+    } else {
+      for (; n < n_real; ++n) iteration(AnyRealTiles{}, n);
+      for (; n <= n_tiles; ++n) iteration(AnyTiles{}, n);
+    }
   }
   vm_wait<0>();                              // nothing may still be writing LDS when the workgroup ends
 
