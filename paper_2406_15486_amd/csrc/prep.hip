@@ -32,6 +32,9 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(GatherParams P) {
   }
   if (P.out_t == nullptr && P.out_rows == nullptr) return;   // only the padded index list was wanted
   if (c0 >= ((cnt + 63) & ~63)) return;   // nothing reads beyond the last partial tile
+  // rows of an earlier segment see no key at or after their end: a tile of the ascending
+  // list that starts there is left alone
+  if (P.key_limit > 0 && P.idx != nullptr && P.idx[(size_t)g * P.idx_stride + c0] >= P.key_limit) return;
   const uint16_t* src = P.src + (size_t)((P.head0 + g) / P.group) * P.S * kHeadDim;
 #pragma unroll
   for (int n = 0; n < 4; ++n) {

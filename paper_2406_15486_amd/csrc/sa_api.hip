@@ -457,7 +457,7 @@ namespace {
 sa_status prepare_heads(const Dims& d, const BlockWs& bw, int granularity, int h0, int nh, size_t n_cand,
                         const void* k, const void* v,
                         const int32_t* col_idx, const int32_t* col_cnt,
-                        const int32_t* slash_idx, const int32_t* slash_cnt, int32_t local_window,
+                        const int32_t* slash_idx, const int32_t* slash_cnt, int32_t local_window, int row_hi,
                         char* ws, hipStream_t st, const int32_t** cnt_used) {
   const SparseWs& w = bw.sp;
   const bool blocks = granularity != 1;
@@ -506,6 +506,7 @@ sa_status prepare_heads(const Dims& d, const BlockWs& bw, int granularity, int h
   G.idx = col_idx; G.cnt = col_cnt; G.idx_stride = d.S;
   G.idx_pad = reinterpret_cast<int32_t*>(ws + w.cidx); G.idx_pad_stride = d.S_pad;
   G.n_out = nh; G.group = d.group; G.head0 = h0; G.S = d.S; G.C_pad = d.S_pad;
+  G.key_limit = row_hi < d.S ? row_hi : 0;     // the rows of this segment end at row_hi: later keys are never read
   if (blocks) return dev(sa::launch_gather_transpose(G, st));
   G.src = static_cast<const uint16_t*>(v);
   G.out_t = reinterpret_cast<uint16_t*>(ws + w.vct);
@@ -611,7 +612,7 @@ sa_status sparse_attn(const sa_shape* shape, int n_chunks, int granularity, cons
       s = prepare_heads(d, bw, granularity, h0, nh, n_cand, k, v,
                         col_idx_all + chunk_off * n_cand, col_cnt_all + chunk_off,
                         slash_idx_all + chunk_off * n_cand, slash_cnt_all + chunk_off,
-                        local_window, ws, st, &cnt_used);
+                        local_window, row_hi, ws, st, &cnt_used);
       if (s != SA_OK) return s;
       const int segs = (n_segments < qtile1 - qtile0) ? n_segments : (qtile1 - qtile0);
       for (int g = 0; g < segs; ++g) {

@@ -59,6 +59,8 @@ struct GatherParams {
   int n_out, group;         // source head of output g is (head0 + g) / group
   int head0;
   int S, C_pad, idx_stride, idx_pad_stride;
+  int key_limit;            // > 0: the list ascends and no reader looks at a key >= key_limit; tiles of 64 list entries
+                            // that start there are not gathered (their idx_pad entries still are written)
 };
 hipError_t launch_gather_transpose(const GatherParams& P, hipStream_t st);
 

@@ -137,6 +137,40 @@ def test_chunked_attn_random_lists(S, Hq, Hkv, C, w, blk):
     assert (tiles.cpu().numpy() > 0).all()
 
 
+@pytest.mark.parametrize("S,C", [(3072, 4), (1000, 3)])
+def test_chunked_attn_reads_nothing_it_did_not_write(S, C):
+    # an early segment gathers only the selected columns its rows can see; whatever the
+    # workspace held before (NaN bit patterns here) must not reach the output
+    import paper_2406_15486_amd as sa
+    _say(f"chunked attn on a poisoned workspace S={S} C={C}")
+    Hq, Hkv, w = 2, 1, 16
+    wl, x = _inputs("glm8k", S, Hq, Hkv, n_sinks=8)
+    rng = np.random.default_rng(S + C)
+    ci = torch.zeros(C, Hq, S, dtype=torch.int32)
+    si = torch.zeros(C, Hq, S, dtype=torch.int32)
+    cc = torch.zeros(C, Hq, dtype=torch.int32)
+    sc = torch.zeros(C, Hq, dtype=torch.int32)
+    for m in range(C):
+        for h in range(Hq):
+            cols = np.sort(rng.choice(S, S // 3, replace=False)).astype(np.int32)
+            offs = np.sort(rng.choice(S, S // 50, replace=False)).astype(np.int32)
+            ci[m, h, :len(cols)] = torch.from_numpy(cols)
+            si[m, h, :len(offs)] = torch.from_numpy(offs)
+            cc[m, h], sc[m, h] = len(cols), len(offs)
+    sh = sa.Shape(1, Hq, Hkv, S)
+    from paper_2406_15486_amd.binding import SA_OP_SPARSE_ATTN
+    need = sa.sa_workspace_bytes(SA_OP_SPARSE_ATTN, sh, n_chunks=C)
+    outs = []
+    for fill in (0x00, 0xFF):
+        ws = torch.full((need,), fill, dtype=torch.uint8, device="cuda")
+        out, lse, _ = sa.sa_sparse_attn_chunked(_dev(x["q"]), _dev(x["k"]), _dev(x["v"]), ci.cuda(), cc.cuda(),
+                                                si.cuda(), sc.cuda(), w, C, workspace=ws, want_lse=True, want_tiles=True)
+        torch.cuda.synchronize()
+        outs.append((out.float().cpu().numpy(), lse.cpu().numpy()))
+    assert np.isfinite(outs[1][0]).all() and np.isfinite(outs[1][1]).all()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
 @pytest.mark.parametrize("name,S,Hq,Hkv,C,gain,blk", [("glm32k", 2048, 2, 1, 2, 5.0, 1), ("glm32k", 4096, 4, 2, 4, None, 128),
                                                       ("glm32k", 3001, 2, 1, 3, 5.0, 1)])
 def test_chunked_pipeline_end_to_end(name, S, Hq, Hkv, C, gain, blk):
