@@ -324,6 +324,22 @@ def test_sparse_attn_random_strips(S, Hq, Hkv, w):
     _sparse_case(wl, x, Ic, Is, w, "sparse random")
 
 
+@pytest.mark.parametrize("n_off", [0, 2, 40])
+def test_sparse_attn_column_counts_around_the_loop_stretches(n_off):
+    """The kernel's tile loop changes form where gathered tiles end and where the schedule
+    ends: column counts of 0 .. 10 tiles of 64 and few / many range tiles put every one of
+    those boundaries at the first, a middle and the last iteration."""
+    S, counts = 1280, [0, 1, 64, 65, 255, 256, 257, 320, 321, 384, 449, 640]
+    _say(f"sparse column counts around the stretches, {n_off} offsets")
+    wl, x = _inputs("glm8k", S=S, Hq=len(counts), Hkv=2, n_sinks=8)
+    rng = np.random.default_rng(n_off)
+    Ic = [np.sort(rng.choice(S, c, replace=False)) for c in counts]
+    Ic[3] = np.arange(65)                                     # the first keys: every query tile sees all of them
+    Ic[7] = np.arange(S - 320, S)                             # the last keys: only the last tiles do
+    Is = [np.sort(rng.choice(S, n_off, replace=False)) for _ in counts]
+    _sparse_case(wl, x, Ic, Is, 1 if n_off else 70, "stretches")
+
+
 def test_sparse_attn_degenerate_strip_sets():
     _say("sparse degenerate sets")
     S, Hq = 700, 4
