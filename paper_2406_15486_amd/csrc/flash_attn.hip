@@ -237,17 +237,18 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   t_base = __builtin_amdgcn_readfirstlane(t_base);
   const int n_tiles = __builtin_amdgcn_readfirstlane((MODE == 2) ? (n_col_tiles + n_rng) : n_sweep);
 
-  // Descriptor of tile t.  A range tile is named by its tile diagonal d: key tile
-  // a64 + 3 - d, which the 256 rows meet at offsets [64 d - 255, 64 d + 63].  The d
-  // values come from a list in global memory; they are fetched (fetch_d) four tiles
-  // ahead of their first use and handed on in scalar registers, so that no phase
-  // waits on a scalar load.
-  // kind of tile t (wave-uniform; no memory access); `real`: t lies inside the schedule
+  // Kind of tile t (wave-uniform; no memory access), and whether t lies inside the schedule.
+  // `kc` is the Stretch the calling iteration belongs to: what it knows at compile time.
   auto is_col = [&](auto kc, int t) __attribute__((always_inline)) -> bool {
     constexpr int KIND = decltype(kc)::KIND;
     return MODE == 2 && (KIND == 1 || (KIND == 0 && t < n_col_tiles));
   };
   auto is_real = [&](auto kc, int t) __attribute__((always_inline)) -> bool { return decltype(kc)::REAL || t < n_tiles; };
+  // Descriptor of tile t.  A range tile is named by its tile diagonal d: key tile
+  // a64 + 3 - d, which the 256 rows meet at offsets [64 d - 255, 64 d + 63].  The d
+  // values come from a list in global memory; they are fetched (fetch_d) four tiles
+  // ahead of their first use and handed on in scalar registers, so that no phase
+  // waits on a scalar load.
   auto fetch_d = [&](auto kc, int t) __attribute__((always_inline)) -> int {
     // read through the constant address space: the list is not written while the kernel
     // runs, and only so does the load stay a scalar one (tracked apart from the vector
