@@ -3,9 +3,9 @@
 pytest captures what a test prints, so a test that works silently for minutes
 looks hung from outside.  ``say`` therefore writes every line three ways: to
 stderr (shown with a failure), to the terminal with capturing suspended, and
-to ``gpurun_out/gpu_test_progress.log`` under the repository root.
+to ``gpu_test_progress.log`` in the results folder ``OUT_DIR`` under the repository root.
 ``record`` keeps measured quantities (strip-set gaps, score errors) in
-``gpurun_out/parity_gaps.json`` so that they can be quoted afterwards.
+``parity_gaps.json`` in the same folder so that they can be quoted afterwards.
 """
 import json
 import os
@@ -43,7 +43,7 @@ def say(msg: str) -> None:
 
 
 def record(key: str, value) -> None:
-    """Store ``value`` (JSON-serialisable) under ``key`` in gpurun_out/parity_gaps.json."""
+    """Store ``value`` (JSON-serialisable) under ``key`` in ``OUT_DIR``/parity_gaps.json."""
     path = os.path.join(OUT_DIR, "parity_gaps.json")
     data = {}
     try:

@@ -14,7 +14,7 @@ closer than that to each other (5e-7 relative at 128K tokens) while the scores
 carry a relative error of up to 1e-4 (their tolerance): a strip can change
 sides when its own score and the cut score are both off by that much, hence
 2e-4, plus what the same error does to alpha * total (a shift of a few ranks,
-below 1e-5).  The measured gaps go to gpurun_out/parity_gaps.json."""
+below 1e-5).  The measured gaps are recorded (``gpu_progress.record``)."""
 
 import numpy as np
 import pytest
