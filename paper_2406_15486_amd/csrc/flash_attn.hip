@@ -62,17 +62,19 @@ enum TileKind : int { TK_PLAIN = 0, TK_CAUSAL = 1, TK_COLIDX = 2, TK_RANGE = 3 }
 // What a stretch of the tile loop knows at compile time about the tiles it touches
 // (the tile of an iteration, the one before and the four ahead).  KIND: nothing (0),
 // all of them gathered-column tiles (1), or none of them (2); REAL: all of them lie
-// inside the schedule.  The loop runs in stretches, so that the long ones carry no
-// per-tile choice between the two kinds of addressing, aux words and activity tests,
-// and no stand-ins for tiles past the end.
-template <int KIND_, bool REAL_>
+// inside the schedule; INTERIOR: the tiles up to the next one hold only keys before the
+// workgroup's first row, so every wave works on them and nothing is masked.  The loop
+// runs in stretches, so that the long ones carry no per-tile choice between the two kinds
+// of addressing, aux words and activity tests, and no stand-ins for tiles past the end.
+template <int KIND_, bool REAL_, bool INTERIOR_ = false>
 struct Stretch {
   static constexpr int KIND = KIND_;
   static constexpr bool REAL = REAL_;
+  static constexpr bool INTERIOR = INTERIOR_;
 };
 using AnyTiles = Stretch<0, false>;
-using AnyRealTiles = Stretch<0, true>;
-using ColTiles = Stretch<1, true>;
+using PlainTiles = Stretch<0, true, true>;       // dense / log-sum-exp sweep below the diagonal
+using ColTiles = Stretch<1, true, true>;
 using RngTiles = Stretch<2, false>;
 using RngRealTiles = Stretch<2, true>;
 
@@ -377,7 +379,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // The aux words are read early (act_words) and looked at later (tile_active), so
   // that the wait for them hides behind MFMAs.
   auto act_words = [&](auto kc, int t, uint32_t& w0, uint32_t& w1) __attribute__((always_inline)) {
-    if (MODE != 2) return;
+    if (MODE != 2 || decltype(kc)::INTERIOR) return;
     const uint32_t* ax = reinterpret_cast<const uint32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
     if (is_col(kc, t)) {
       w0 = ax[0];
@@ -387,6 +389,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
     }
   };
   auto tile_active = [&](auto kc, int t, int d, uint32_t w0, uint32_t w1) __attribute__((always_inline)) -> bool {
+    if (decltype(kc)::INTERIOR) return true;
     bool act;
     const int j0 = first_key(kc, t, d);
     if (is_col(kc, t)) {
@@ -486,7 +489,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // ---- the softmax phase: mask, online softmax (one query per lane), bf16 --------
   auto step_softmax = [&](auto kc, int t, int d) __attribute__((always_inline)) {
     const int j0 = first_key(kc, t, d);
-    const int kind = is_col(kc, t) ? TK_COLIDX : (MODE == 2) ? TK_RANGE : (j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
+    constexpr bool INTERIOR = decltype(kc)::INTERIOR;
+    const int kind = is_col(kc, t) ? TK_COLIDX : (MODE == 2) ? TK_RANGE : (!INTERIOR && j0 + BK - 1 > i0) ? TK_CAUSAL : TK_PLAIN;
     const int buf = t & (NSTAGE - 1);
     // Mask: one 32-bit pattern per lane and 32-key half, bit b <-> key
     // j0 + 32 sb + 8 hf + b of the lane's 16 (b = 0..7, 16..23), set = keep.  The
@@ -505,7 +509,7 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       }
     } else if (MODE == 2 && kind == TK_COLIDX) {
       const int32_t* il = reinterpret_cast<const int32_t*>(smem + OFF_A + (t & (NAUX - 1)) * AUX_B);
-      if (il[BK - 1] > iw0) {              // only the last gathered tiles reach past a row: keep index <= query
+      if (!INTERIOR && il[BK - 1] > iw0) {   // only the last gathered tiles reach past a row: keep index <= query
         masked = true;
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
@@ -742,12 +746,17 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
   // wave of every SIMD on the matrix pipe while the other is on the vector pipe.
   // (The loop is written out once per group: one loop that picks the phase at run
   // time keeps the registers of both phases alive everywhere and spills.)
-  // Iteration n touches tiles n - 1 .. n + 4.  In the strip-masked kernel the iterations
-  // n + 4 < n_col_tiles see gathered tiles only, the iterations n > n_col_tiles range
-  // tiles only; the few in between take the general form.  The iterations n + 4 <
-  // n_tiles see no tile past the end of the schedule.
-  const int n_gen0 = (MODE == 2) ? max(n_col_tiles - 4, 0) : 0;            // first iteration of the general form
-  const int n_gen1 = (MODE == 2) ? min(n_col_tiles, n_tiles) : -1;         // its last
+  // Iteration n touches tiles n - 1 .. n + 4 and decides on the work of tiles n and n + 1.
+  // Strip-masked kernel: the selected keys that are not before the workgroup's first row
+  // (at most 256) lie in the last five gathered tiles, so the iterations n + 1 <
+  // n_col_tiles - 5 see gathered tiles only, with work for every wave and nothing to mask;
+  // the iterations n > n_col_tiles see range tiles only; the few in between take the
+  // general form.  Dense and log-sum-exp sweeps: the tiles below key tile a64 (the one
+  // that holds the first row) are interior.  The iterations n + 4 < n_tiles see no tile
+  // past the end of the schedule.
+  const int n_gen0 = (MODE == 2) ? max(n_col_tiles - 6, 0)                 // first iteration of the general form
+                                 : max(min(a64 - t_base - 1, n_tiles - 4), 0);
+  const int n_gen1 = (MODE == 2) ? min(n_col_tiles, n_tiles) : n_tiles;    // its last
   const int n_real = n_tiles - 4;                                          // first iteration that may see a tile past the end
   if (grp == 0) {
     auto iteration = [&](auto kc, int n) __attribute__((always_inline)) {
@@ -767,8 +776,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       for (; n < n_real; ++n) iteration(RngRealTiles{}, n);
       for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
     } else {
-      for (; n < n_real; ++n) iteration(AnyRealTiles{}, n);
-      for (; n <= n_tiles; ++n) iteration(AnyTiles{}, n);
+      for (; n < n_gen0; ++n) iteration(PlainTiles{}, n);
+      for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
     }
   } else {
     int dprev = 0;                           // tile diagonal of tile n - 1
@@ -787,8 +796,8 @@ __global__ __launch_bounds__(NT, (MODE == 1) ? 4 : 1) void flash_kernel(FlashPar
       for (; n < n_real; ++n) iteration(RngRealTiles{}, n);
       for (; n <= n_tiles; ++n) iteration(RngTiles{}, n);
     } else {
-      for (; n < n_real; ++n) iteration(AnyRealTiles{}, n);
-      for (; n <= n_tiles; ++n) iteration(AnyTiles{}, n);
+      for (; n < n_gen0; ++n) iteration(PlainTiles{}, n);
+      for (; n <= n_gen1; ++n) iteration(AnyTiles{}, n);
     }
   }
   vm_wait<0>();                              // nothing may still be writing LDS when the workgroup ends
