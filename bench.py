@@ -20,8 +20,9 @@ with the inputs already resident in HBM.  Prints ONE JSON line:
 Everything else on the line (per-stage times, the in-library dense kernel,
 speedup, kept fractions, useful rate, alpha sweep with the recall of each mask,
 the same workload at block granularity and with two chunks, separate column /
-slash thresholds on heads of one pattern each, the peaks this GPU reaches on a
-bare MFMA loop and a plain copy) is context.  --sampling-study replaces the run
+slash thresholds on heads of one pattern each, the same step replayed from a
+captured HIP graph, the peaks this GPU reaches on a bare MFMA loop and a plain
+copy) is context.  --sampling-study replaces the run
 by a comparison of sampled against full scores.
 """
 from __future__ import annotations
@@ -253,6 +254,8 @@ def main() -> int:
     ap.add_argument("--no-alpha-grid", action="store_true",
                     help="skip the grid of separate column / slash thresholds on the three head patterns")
     ap.add_argument("--no-peaks", action="store_true", help="skip the MFMA / copy peak probes")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="skip the replay of the same steps from a captured HIP graph")
     ap.add_argument("--heads-per-pass", type=int, default=0,
                     help="bound the workspace (long sequences): stage 1 and the attention take this many heads at a "
                          "time (sa_sparse_attn_partitioned); 0 = all heads at once")
@@ -526,6 +529,30 @@ def main() -> int:
             del pq, pk, pv, p_dense_lse
     sa.sa_profile_enable(False)
 
+    # ---- the same step replayed from a HIP graph (launch overhead; matters at short lengths) ----
+    graph_ms = None
+    if not args.no_graph and not args.heads_per_pass:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            plan.run(q, k, v, args.alpha, args.alpha, w)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            plan.run(q, k, v, args.alpha, args.alpha, w)
+        g.replay()
+        torch.cuda.synchronize()
+        gev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for e0, e1 in gev:
+            e0.record()
+            g.replay()
+            e1.record()
+        torch.cuda.synchronize()
+        graph_ms = float(np.median([e0.elapsed_time(e1) for e0, e1 in gev]))
+        log(f"graph replay: {graph_ms:.3f} ms/step (eager {ms_median:.3f})")
+        del g
+
     # ---- what this GPU reaches on a bare MFMA loop and on a plain copy ---------------------
     peaks = None
     if not args.no_peaks:
@@ -600,6 +627,7 @@ def main() -> int:
         "timing": {"value": "median of per-step HIP-event durations on the launch stream",
                    "ms_per_step": "wall-clock mean over the same steps", "step_ms": step_ms},
         "stage_ms": stage_ms,
+        "graph_replay_ms_per_step": graph_ms,
         "useful_tflops": useful_tflops,
         "schedule_slot_fraction": slots / dense_tiles,
         "idle_slot_share": 1.0 - float(tiles.sum()) / slots,
