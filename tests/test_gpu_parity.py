@@ -340,6 +340,22 @@ def test_sparse_attn_column_counts_around_the_loop_stretches(n_off):
     _sparse_case(wl, x, Ic, Is, 1 if n_off else 70, "stretches")
 
 
+@pytest.mark.parametrize("S,fc,fs", [(1500, 0.7, 0.6), (1024, 0.95, 0.9), (2304, 0.5, 0.8)])
+def test_sparse_attn_nearly_full_lists(S, fc, fs):
+    """Lists so full that most keys are selected columns AND most offsets are kept: every
+    pair is still counted once (a key taken by the column pass is masked out of its range
+    tile), whatever the two passes cost."""
+    _say(f"sparse nearly full lists S={S} columns {fc} offsets {fs}")
+    Hq = 3
+    wl, x = _inputs("glm8k", S=S, Hq=Hq, Hkv=1, n_sinks=8)
+    rng = np.random.default_rng(S)
+    Ic = [np.sort(rng.choice(S, int(fc * S), replace=False)) for _ in range(Hq)]
+    Is = [np.sort(rng.choice(S, int(fs * S), replace=False)) for _ in range(Hq)]
+    Ic[2] = Ic[2][:S // 50]
+    Is[2] = Is[2][:S // 100]
+    _sparse_case(wl, x, Ic, Is, 16, "nearly full")
+
+
 def test_sparse_attn_degenerate_strip_sets():
     _say("sparse degenerate sets")
     S, Hq = 700, 4
